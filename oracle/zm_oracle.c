@@ -1,0 +1,612 @@
+/*
+ * zm_oracle.c -- reference codec for compressed bf16 expert weights.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain checker that the
+ * tests, the smoke check and the benchmark's CPU-baseline leg run; the
+ * product library never includes, links or calls it, and it shares no code,
+ * table or header with the product library.
+ *
+ * What it follows (ZipMoE, arXiv 2601.21198):
+ *   - Sec. 2.2 "BF16 Parameters": a bf16 word is 1 sign, 8 exponent and 7
+ *     mantissa bits.
+ *   - Sec. 3.1 "Offline Initialization": bit-field decomposition into
+ *     exponent bits and sign-mantissa bits; the exponent bits are cut into
+ *     K shards that are compressed one by one (E-chunks); the sign-mantissa
+ *     bits are packed one byte per value (SM-chunks); everything plus the
+ *     metadata is serialised into one binary object.
+ *   - Sec. 3.3 "Memory-Coalesced Tensor Recovery Kernel": the inverse step,
+ *     exponent byte + sign-mantissa byte -> bf16 word.
+ *   - Sec. 6 "Other Compressors": the compressor that turns exponent bytes
+ *     into an E-chunk is pluggable.  The backend defined here is a canonical,
+ *     length-limited prefix code (one codebook per tensor).  Its bitstream
+ *     layout is not in the paper; it is fixed by this file and described in
+ *     the comments below, step by step.
+ *
+ * Every function is written for readability, one step at a time: bits are
+ * handled one at a time, the code-length optimiser is an exhaustive dynamic
+ * programme over the Kraft budget, and nothing is blocked, fused or
+ * table-accelerated.
+ *
+ * Parity status: every function here is pinned by tests that do not go
+ * through this file's own arithmetic (closed forms, brute force, the exact
+ * round-trip property, the entropy bound of Sec. 2.2); nothing is unpinned.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- layout constants of the serialised object ------------------------- */
+
+#define ZO_MAGIC        0x454F4D5Au   /* bytes 'Z','M','O','E' */
+#define ZO_VERSION      1u
+#define ZO_HEADER_BYTES 128u
+#define ZO_LANES        64u   /* per-stream lanes                              */
+#define ZO_RUN          8u    /* consecutive values one lane owns in a tile     */
+#define ZO_TILE         512u  /* ZO_LANES * ZO_RUN values                       */
+#define ZO_MAX_LEN      12    /* longest code the format admits                 */
+
+enum { ZO_OK = 0, ZO_E_ARG = -1, ZO_E_SIZE = -2, ZO_E_FORMAT = -3, ZO_E_NOMEM = -4 };
+
+enum { ZO_MODE_CODED = 0, ZO_MODE_RAW = 1 };
+
+/* header field offsets (bytes) */
+enum {
+    H_MAGIC = 0, H_VERSION = 4, H_NVALUES = 8, H_CHUNK = 16, H_STREAM = 20,
+    H_NCHUNKS = 24, H_L = 28, H_R = 32, H_NPRESENT = 36, H_PADSYM = 40,
+    H_LEN_OFF = 48, H_LUT_OFF = 56, H_TABLE_OFF = 64, H_SM_OFF = 72,
+    H_E_OFF = 80, H_BLOB_SIZE = 88
+};
+
+static uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+static void put32(uint8_t *p, uint32_t v) { for (int i = 0; i < 4; i++) p[i] = (uint8_t)(v >> (8 * i)); }
+static void put64(uint8_t *p, uint64_t v) { for (int i = 0; i < 8; i++) p[i] = (uint8_t)(v >> (8 * i)); }
+static uint32_t get32(const uint8_t *p) { uint32_t v = 0; for (int i = 0; i < 4; i++) v |= (uint32_t)p[i] << (8 * i); return v; }
+static uint64_t get64(const uint8_t *p) { uint64_t v = 0; for (int i = 0; i < 8; i++) v |= (uint64_t)p[i] << (8 * i); return v; }
+
+/* ---- Sec. 2.2 / Sec. 3.1: bit-field decomposition ---------------------- */
+
+/* word = s eeeeeeee mmmmmmm (bit 15 .. bit 0).
+ * exponent byte  = the 8 e bits;
+ * sign-mantissa byte = s in bit 7, the 7 m bits in bits 6..0.               */
+void zo_split(const uint16_t *w, size_t n, uint8_t *e, uint8_t *sm)
+{
+    for (size_t i = 0; i < n; i++) {
+        unsigned sign = (w[i] >> 15) & 1u;
+        unsigned expo = (w[i] >> 7) & 0xFFu;
+        unsigned mant = w[i] & 0x7Fu;
+        e[i] = (uint8_t)expo;
+        sm[i] = (uint8_t)((sign << 7) | mant);
+    }
+}
+
+/* Sec. 3.3: the recovery step, the inverse of zo_split. */
+void zo_merge(const uint8_t *e, const uint8_t *sm, size_t n, uint16_t *w)
+{
+    for (size_t i = 0; i < n; i++) {
+        unsigned sign = (sm[i] >> 7) & 1u;
+        unsigned mant = sm[i] & 0x7Fu;
+        unsigned expo = e[i];
+        w[i] = (uint16_t)((sign << 15) | (expo << 7) | mant);
+    }
+}
+
+void zo_histogram(const uint8_t *e, size_t n, uint64_t hist[256])
+{
+    for (int s = 0; s < 256; s++) hist[s] = 0;
+    for (size_t i = 0; i < n; i++) hist[e[i]]++;
+}
+
+/* ---- codebook: optimal length-limited prefix-code lengths -------------- */
+
+/* Definition used: among all assignments len[s] in 1..max_len for the
+ * symbols with hist[s] > 0 that satisfy the Kraft inequality
+ *      sum_s 2^(-len[s]) <= 1,
+ * pick one that minimises sum_s hist[s]*len[s].  A prefix code with those
+ * lengths exists exactly when Kraft holds, so this is the optimal
+ * length-limited prefix code.  The search is an exact dynamic programme:
+ * symbols are taken one by one, the state is the Kraft budget spent so far
+ * in units of 2^(-max_len).  Absent symbols get length 0.
+ * Returns ZO_E_ARG if max_len is outside 1..ZO_MAX_LEN or the present
+ * symbols cannot fit (more than 2^max_len of them).                        */
+int zo_code_lengths(const uint64_t hist[256], int max_len, uint8_t len[256])
+{
+    if (max_len < 1 || max_len > ZO_MAX_LEN) return ZO_E_ARG;
+    int sym[256], n = 0;
+    for (int s = 0; s < 256; s++) { len[s] = 0; if (hist[s] > 0) sym[n++] = s; }
+    if (n == 0) return ZO_OK;
+    const uint32_t budget = 1u << max_len;
+    if ((uint32_t)n > budget) return ZO_E_ARG;
+
+    const uint64_t INF = UINT64_MAX;
+    /* cost[i][k]: least sum of hist*len over the first i present symbols
+     * whose Kraft terms add up to exactly k units; pick[i][k]: the length
+     * given to symbol i-1 on that best path.                                */
+    size_t row = (size_t)budget + 1;
+    uint64_t *cost = (uint64_t *)malloc((size_t)(n + 1) * row * sizeof(uint64_t));
+    uint8_t *pick = (uint8_t *)malloc((size_t)(n + 1) * row);
+    if (!cost || !pick) { free(cost); free(pick); return ZO_E_NOMEM; }
+    for (size_t j = 0; j < (size_t)(n + 1) * row; j++) { cost[j] = INF; pick[j] = 0; }
+    cost[0] = 0;
+    for (int i = 0; i < n; i++) {
+        for (uint32_t k = 0; k <= budget; k++) {
+            uint64_t c = cost[(size_t)i * row + k];
+            if (c == INF) continue;
+            for (int l = 1; l <= max_len; l++) {
+                uint32_t k2 = k + (1u << (max_len - l));
+                if (k2 > budget) continue;
+                uint64_t c2 = c + hist[sym[i]] * (uint64_t)l;
+                size_t j = (size_t)(i + 1) * row + k2;
+                if (c2 < cost[j]) { cost[j] = c2; pick[j] = (uint8_t)l; }
+            }
+        }
+    }
+    uint32_t best_k = 0; uint64_t best = INF;
+    for (uint32_t k = 0; k <= budget; k++)
+        if (cost[(size_t)n * row + k] < best) { best = cost[(size_t)n * row + k]; best_k = k; }
+    uint32_t k = best_k;
+    for (int i = n; i >= 1; i--) {
+        int l = pick[(size_t)i * row + k];
+        len[sym[i - 1]] = (uint8_t)l;
+        k -= 1u << (max_len - l);
+    }
+    free(cost); free(pick);
+    return ZO_OK;
+}
+
+/* Canonical code assignment.  Present symbols are ordered by (length
+ * ascending, symbol value ascending); the first gets code 0, each next one
+ * gets (previous code + 1) shifted left by the increase in length.  code[s]
+ * holds the code as a number whose most significant of len[s] bits is the
+ * first bit on the wire.  Returns the number of present symbols.           */
+int zo_canonical(const uint8_t len[256], uint16_t code[256])
+{
+    int n = 0;
+    uint32_t next = 0; int prev_len = 0;
+    for (int s = 0; s < 256; s++) code[s] = 0;
+    for (int l = 1; l <= ZO_MAX_LEN; l++) {
+        for (int s = 0; s < 256; s++) {
+            if (len[s] != l) continue;
+            if (n > 0) next = (next + 1) << (l - prev_len);
+            code[s] = (uint16_t)next;
+            prev_len = l;
+            n++;
+        }
+    }
+    return n;
+}
+
+/* Integer Kraft sum in units of 2^(-ZO_MAX_LEN); a complete code gives
+ * exactly 2^ZO_MAX_LEN.  Lengths outside 0..ZO_MAX_LEN give UINT32_MAX.    */
+uint32_t zo_kraft_units(const uint8_t len[256])
+{
+    uint32_t k = 0;
+    for (int s = 0; s < 256; s++) {
+        if (len[s] > ZO_MAX_LEN) return UINT32_MAX;
+        if (len[s]) k += 1u << (ZO_MAX_LEN - len[s]);
+    }
+    return k;
+}
+
+static int max_code_len(const uint8_t len[256])
+{
+    int L = 1;
+    for (int s = 0; s < 256; s++) if (len[s] > L) L = len[s];
+    return L;
+}
+
+/* symbols per round: how many symbols every lane decodes between two refill
+ * points.  A round never consumes more than 32 bits.                       */
+static uint32_t round_symbols(int L) { return L <= 8 ? 4u : 2u; }
+
+/* the symbol that fills positions past the end of a stream: the first one in
+ * canonical order, whose code is all zero bits                              */
+static int pad_symbol(const uint8_t len[256])
+{
+    for (int l = 1; l <= ZO_MAX_LEN; l++)
+        for (int s = 0; s < 256; s++) if (len[s] == l) return s;
+    return 0;
+}
+
+/* ---- one stream: at most stream_values consecutive values -------------- */
+/*
+ * A stream is cut into tiles of 512 values.  In every tile lane j (0..63)
+ * owns values 8j .. 8j+7, so over the stream a lane owns 8*tiles symbols,
+ * taken tile after tile.  Positions at or past the stream's end hold the pad
+ * symbol.
+ *
+ * Each lane has a bitstream of its own: the codes of its symbols one after
+ * the other, the first bit of a code in the lowest free bit (LSB first),
+ * packed into 32-bit little-endian words and continued with zero bits.
+ *
+ * The 64 lane bitstreams are woven into one word sequence in the order a
+ * lock-step decoder needs them.  Decoding goes in rounds; in a round every
+ * lane decodes R symbols (R = 4 when the longest code has at most 8 bits,
+ * else 2, so that a round uses at most 32 bits).  At the start of every
+ * round a lane holds words q and q+1 of its bitstream, q = (bits it has used
+ * so far) / 32.  Hence:
+ *   - the sequence begins with words 0 and 1 of lane 0, then of lane 1, ...
+ *     (128 words);
+ *   - after every round but the last, the lanes whose q went up by one take,
+ *     in lane order, the next words of the sequence (each lane its own next
+ *     word).
+ * The sequence is padded with zero words to a multiple of 4 words.
+ */
+
+/* worst-case number of 32-bit words of one coded stream */
+static size_t stream_words_bound(uint32_t stream_values)
+{
+    size_t tiles = (stream_values + ZO_TILE - 1) / ZO_TILE;
+    size_t bits_per_lane = tiles * ZO_RUN * ZO_MAX_LEN;
+    return ZO_LANES * (2 + (bits_per_lane + 31) / 32) + 4;
+}
+
+/* Encodes exponents e[0..n) (n <= stream_values) into out[]; returns words
+ * written (a multiple of 4).                                               */
+static size_t encode_stream(const uint8_t *e, uint32_t n, const uint8_t len[256],
+                            const uint16_t code[256], int L, int pad, uint32_t *out)
+{
+    const uint32_t R = round_symbols(L);
+    const uint32_t tiles = (n + ZO_TILE - 1) / ZO_TILE;
+    const uint32_t nsym = tiles * ZO_RUN;        /* symbols per lane */
+    const uint32_t rounds = nsym / R;
+    const size_t lane_words = 2 + ((size_t)nsym * ZO_MAX_LEN + 31) / 32 + 1;
+
+    /* 1. every lane's own bitstream, as words, plus the bit position after
+     *    each of its symbols                                                */
+    uint32_t *words = (uint32_t *)calloc(ZO_LANES * lane_words, sizeof(uint32_t));
+    uint32_t *used_after = (uint32_t *)calloc((size_t)ZO_LANES * (nsym + 1), sizeof(uint32_t));
+    for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
+        uint32_t pos = 0;
+        for (uint32_t j = 0; j < nsym; j++) {
+            uint32_t t = j / ZO_RUN, i = j % ZO_RUN;
+            uint32_t idx = t * ZO_TILE + lane * ZO_RUN + i;
+            int s = idx < n ? e[idx] : pad;
+            for (int b = len[s] - 1; b >= 0; b--) {       /* first wire bit = top bit of the code */
+                uint32_t bit = (code[s] >> b) & 1u;
+                words[lane * lane_words + pos / 32] |= bit << (pos % 32);
+                pos++;
+            }
+            used_after[(size_t)lane * (nsym + 1) + j + 1] = pos;
+        }
+    }
+    /* 2. weave */
+    size_t w = 0;
+    uint32_t have[ZO_LANES];
+    for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
+        out[w++] = words[lane * lane_words + 0];
+        out[w++] = words[lane * lane_words + 1];
+        have[lane] = 2;
+    }
+    for (uint32_t r = 0; r + 1 < rounds; r++) {
+        for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
+            uint32_t used = used_after[(size_t)lane * (nsym + 1) + (r + 1) * R];
+            uint32_t q = used / 32;
+            while (have[lane] < q + 2) {               /* at most once: a round uses <= 32 bits */
+                out[w++] = words[lane * lane_words + have[lane]];
+                have[lane]++;
+            }
+        }
+    }
+    while (w % 4) out[w++] = 0;
+    free(words); free(used_after);
+    return w;
+}
+
+/* read bit number pos of a lane's bitstream held as a word list */
+static int lane_bit(const uint32_t *lane_words, uint32_t pos)
+{
+    return (int)((lane_words[pos / 32] >> (pos % 32)) & 1u);
+}
+
+/* Decodes one stream.  words/n_words: the woven sequence as stored (padding
+ * included).  Writes n exponent bytes.  Checks everything it can: that every
+ * bit it reads lies in a word the lane holds, that every code is a code of
+ * the book, that pad positions hold the pad symbol, and that the sequence
+ * has exactly the words the schedule asks for plus zero padding up to a
+ * multiple of 4.                                                           */
+static int decode_stream(const uint32_t *words, size_t n_words, uint32_t n,
+                         const uint8_t len[256], const uint16_t code[256],
+                         int L, int pad, uint8_t *e)
+{
+    const uint32_t R = round_symbols(L);
+    const uint32_t tiles = (n + ZO_TILE - 1) / ZO_TILE;
+    const uint32_t nsym = tiles * ZO_RUN;
+    const uint32_t rounds = nsym / R;
+    const size_t cap = 2 + ((size_t)nsym * ZO_MAX_LEN + 31) / 32 + 1;
+    int rc = ZO_OK;
+
+    if (n_words < 2 * ZO_LANES) return ZO_E_FORMAT;
+    uint32_t *mine = (uint32_t *)calloc(ZO_LANES * cap, sizeof(uint32_t));   /* words each lane holds */
+    uint32_t have[ZO_LANES], used[ZO_LANES];
+    size_t w = 0;
+    for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
+        mine[lane * cap + 0] = words[w++];
+        mine[lane * cap + 1] = words[w++];
+        have[lane] = 2; used[lane] = 0;
+    }
+    for (uint32_t r = 0; r < rounds && rc == ZO_OK; r++) {
+        for (uint32_t lane = 0; lane < ZO_LANES && rc == ZO_OK; lane++) {
+            for (uint32_t k = 0; k < R; k++) {
+                /* walk the code one bit at a time until it equals a code of the book */
+                uint32_t acc = 0; int l = 0, found = -1;
+                while (found < 0 && l < L) {
+                    if (used[lane] / 32 >= have[lane]) { rc = ZO_E_FORMAT; break; }
+                    acc = (acc << 1) | (uint32_t)lane_bit(mine + lane * cap, used[lane]);
+                    used[lane]++; l++;
+                    for (int s = 0; s < 256; s++)
+                        if (len[s] == l && code[s] == acc) { found = s; break; }
+                }
+                if (rc != ZO_OK) break;
+                if (found < 0) { rc = ZO_E_FORMAT; break; }
+                uint32_t j = r * R + k;
+                uint32_t idx = (j / ZO_RUN) * ZO_TILE + lane * ZO_RUN + (j % ZO_RUN);
+                if (idx < n) e[idx] = (uint8_t)found;
+                else if (found != pad) { rc = ZO_E_FORMAT; break; }
+            }
+        }
+        if (rc != ZO_OK || r + 1 == rounds) break;
+        for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
+            uint32_t q = used[lane] / 32;
+            while (have[lane] < q + 2) {
+                if (w >= n_words) { rc = ZO_E_FORMAT; break; }
+                mine[lane * cap + have[lane]] = words[w++];
+                have[lane]++;
+            }
+            if (rc != ZO_OK) break;
+        }
+    }
+    if (rc == ZO_OK) {
+        if (n_words - w >= 4 || n_words % 4) rc = ZO_E_FORMAT;
+        for (size_t j = w; j < n_words && rc == ZO_OK; j++) if (words[j] != 0) rc = ZO_E_FORMAT;
+    }
+    free(mine);
+    return rc;
+}
+
+/* ---- the serialised tensor --------------------------------------------- */
+/*
+ * byte 0    header, 128 bytes (fields at the H_* offsets, the rest zero)
+ * byte 128  code_len[256]: code length of every exponent value, 0 = absent
+ *           (canonical codes follow from the lengths)
+ * byte 384  decode table: 2^L entries of 16 bits, L = longest code length
+ *           (at least 1).  Entry x describes the code that the L stream bits
+ *           x (bit 0 = first wire bit) begin with: low byte = symbol, high
+ *           byte = its length.  Bit patterns that begin with no code (only
+ *           when fewer than two symbols are present) name the pad symbol
+ *           with length 1.
+ * then      chunk table, 16-byte aligned: n_chunks+1 entries of 64 bits;
+ *           entry c = byte offset of E-chunk c from the start of the object
+ *           (a multiple of 16) + the chunk's mode in the low 4 bits; the last
+ *           entry is the end offset of the last E-chunk, mode bits 0
+ * then      SM section, 256-byte aligned: n_values sign-mantissa bytes in
+ *           tensor order
+ * then      E-chunks, the first 256-byte aligned, each 16-byte aligned.
+ *           Chunk c covers values [c*C, min(n, (c+1)*C)).
+ *             mode RAW:   the chunk's exponent bytes, zero padded to 16
+ *             mode CODED: u32 n_values, u32 n_streams S, u32 total bytes,
+ *                         u32 0, then u32 stream_off[S+1] (byte offsets from
+ *                         the chunk start, zero padded to 16), then the S
+ *                         streams; stream s covers values [s*W, (s+1)*W) of
+ *                         the chunk
+ *           A chunk is stored RAW when its coded form would not be smaller.
+ * The object's total size is a multiple of 256.
+ */
+
+size_t zo_encode_bound(size_t n_values, uint32_t chunk_values, uint32_t stream_values)
+{
+    (void)stream_values;
+    size_t chunks = chunk_values ? (n_values + chunk_values - 1) / chunk_values : 0;
+    return 384 + 2 * 4096 + 16 + 8 * (chunks + 1) + 256 + n_values + 256 + n_values + 16 * chunks + 512;
+}
+
+static int check_geometry(uint32_t C, uint32_t W)
+{
+    if (W == 0 || C == 0) return 0;
+    if (W % ZO_TILE) return 0;
+    if (C % W) return 0;
+    return 1;
+}
+
+int zo_encode(const uint16_t *w, size_t n, uint32_t C, uint32_t W,
+              const uint8_t len[256], uint8_t *blob, size_t cap, size_t *size_out)
+{
+    if (!check_geometry(C, W)) return ZO_E_ARG;
+    if (zo_kraft_units(len) > (1u << ZO_MAX_LEN)) return ZO_E_ARG;
+    if (cap < zo_encode_bound(n, C, W)) return ZO_E_SIZE;
+
+    uint8_t *e = (uint8_t *)malloc(n ? n : 1), *sm = (uint8_t *)malloc(n ? n : 1);
+    if (!e || !sm) { free(e); free(sm); return ZO_E_NOMEM; }
+    zo_split(w, n, e, sm);
+    for (size_t i = 0; i < n; i++) if (len[e[i]] == 0) { free(e); free(sm); return ZO_E_ARG; }
+
+    uint16_t code[256];
+    int n_present = zo_canonical(len, code);
+    int L = max_code_len(len);
+    int pad = pad_symbol(len);
+    size_t K = (n + C - 1) / C;
+
+    uint64_t len_off = ZO_HEADER_BYTES;
+    uint64_t lut_off = len_off + 256;
+    uint64_t table_off = round_up(lut_off + 2 * ((uint64_t)1 << L), 16);
+    uint64_t sm_off = round_up(table_off + 8 * (K + 1), 256);
+    uint64_t e_off = round_up(sm_off + n, 256);
+
+    memset(blob, 0, e_off);
+    memcpy(blob + len_off, len, 256);
+    /* decode table, by its definition: for every L-bit pattern find the code it begins with */
+    for (uint32_t x = 0; x < (1u << L); x++) {
+        int sym = pad, sl = 1;
+        for (int s = 0; s < 256; s++) {
+            if (!len[s]) continue;
+            int match = 1;
+            for (int b = 0; b < len[s]; b++) {
+                uint32_t wire_bit = (x >> b) & 1u;
+                uint32_t code_bit = (code[s] >> (len[s] - 1 - b)) & 1u;
+                if (wire_bit != code_bit) { match = 0; break; }
+            }
+            if (match) { sym = s; sl = len[s]; break; }
+        }
+        blob[lut_off + 2 * x] = (uint8_t)sym;
+        blob[lut_off + 2 * x + 1] = (uint8_t)sl;
+    }
+    memcpy(blob + sm_off, sm, n);
+
+    uint32_t *tmp = (uint32_t *)malloc(stream_words_bound(W) * sizeof(uint32_t));
+    uint64_t pos = e_off;
+    for (size_t c = 0; c < K; c++) {
+        uint32_t cn = (uint32_t)((n - c * C) < C ? (n - c * C) : C);
+        uint32_t S = (cn + W - 1) / W;
+        uint64_t raw_bytes = round_up(cn, 16);
+        /* coded form, built in place */
+        uint64_t head = 16 + round_up(4 * ((uint64_t)S + 1), 16);
+        uint64_t at = head;
+        uint8_t *base = blob + pos;
+        int fits = 1;
+        memset(base, 0, head);
+        for (uint32_t s = 0; s < S && fits; s++) {
+            uint32_t sn = (cn - s * W) < W ? (cn - s * W) : W;
+            size_t nw = encode_stream(e + c * C + (size_t)s * W, sn, len, code, L, pad, tmp);
+            put32(base + 16 + 4 * s, (uint32_t)at);
+            if (at + 4 * nw >= raw_bytes) { fits = 0; break; }
+            for (size_t j = 0; j < nw; j++) put32(base + at + 4 * j, tmp[j]);
+            at += 4 * nw;
+        }
+        if (fits && at < raw_bytes) {
+            put32(base + 0, cn); put32(base + 4, S); put32(base + 8, (uint32_t)at); put32(base + 12, 0);
+            put32(base + 16 + 4 * S, (uint32_t)at);
+            put64(blob + table_off + 8 * c, pos | ZO_MODE_CODED);
+            pos += at;
+        } else {
+            memset(base, 0, raw_bytes);
+            memcpy(base, e + c * C, cn);
+            put64(blob + table_off + 8 * c, pos | ZO_MODE_RAW);
+            pos += raw_bytes;
+        }
+    }
+    put64(blob + table_off + 8 * K, pos);
+    uint64_t total = round_up(pos, 256);
+    memset(blob + pos, 0, total - pos);
+
+    put32(blob + H_MAGIC, ZO_MAGIC); put32(blob + H_VERSION, ZO_VERSION);
+    put64(blob + H_NVALUES, n); put32(blob + H_CHUNK, C); put32(blob + H_STREAM, W);
+    put32(blob + H_NCHUNKS, (uint32_t)K); put32(blob + H_L, (uint32_t)L);
+    put32(blob + H_R, round_symbols(L)); put32(blob + H_NPRESENT, (uint32_t)n_present);
+    put32(blob + H_PADSYM, (uint32_t)pad);
+    put64(blob + H_LEN_OFF, len_off); put64(blob + H_LUT_OFF, lut_off);
+    put64(blob + H_TABLE_OFF, table_off); put64(blob + H_SM_OFF, sm_off);
+    put64(blob + H_E_OFF, e_off); put64(blob + H_BLOB_SIZE, total);
+    *size_out = total;
+    free(tmp); free(e); free(sm);
+    return ZO_OK;
+}
+
+/* number of values stored in a serialised tensor, or 0 if the header is bad */
+uint64_t zo_blob_values(const uint8_t *blob, size_t size)
+{
+    if (size < ZO_HEADER_BYTES || get32(blob + H_MAGIC) != ZO_MAGIC) return 0;
+    return get64(blob + H_NVALUES);
+}
+
+/* Decodes chunks [c0, c1) of a serialised tensor into out (indexed from the
+ * tensor's first value: chunk c lands at out[c*C ...]).  Validates the
+ * header, the codebook and every structure it walks.                       */
+int zo_decode_chunks(const uint8_t *blob, size_t size, size_t c0, size_t c1, uint16_t *out)
+{
+    if (size < ZO_HEADER_BYTES) return ZO_E_FORMAT;
+    if (get32(blob + H_MAGIC) != ZO_MAGIC || get32(blob + H_VERSION) != ZO_VERSION) return ZO_E_FORMAT;
+    uint64_t n = get64(blob + H_NVALUES);
+    uint32_t C = get32(blob + H_CHUNK), W = get32(blob + H_STREAM);
+    uint64_t K = get32(blob + H_NCHUNKS);
+    int L = (int)get32(blob + H_L);
+    uint64_t len_off = get64(blob + H_LEN_OFF), lut_off = get64(blob + H_LUT_OFF);
+    uint64_t table_off = get64(blob + H_TABLE_OFF), sm_off = get64(blob + H_SM_OFF);
+    uint64_t e_off = get64(blob + H_E_OFF), total = get64(blob + H_BLOB_SIZE);
+    if (!check_geometry(C, W)) return ZO_E_FORMAT;
+    if (K != (n + C - 1) / C) return ZO_E_FORMAT;
+    if (total > size || total % 256) return ZO_E_FORMAT;
+    if (len_off != ZO_HEADER_BYTES || lut_off != len_off + 256) return ZO_E_FORMAT;
+    if (L < 1 || L > ZO_MAX_LEN) return ZO_E_FORMAT;
+    if (table_off != round_up(lut_off + 2 * ((uint64_t)1 << L), 16)) return ZO_E_FORMAT;
+    if (sm_off != round_up(table_off + 8 * (K + 1), 256)) return ZO_E_FORMAT;
+    if (e_off != round_up(sm_off + n, 256) || e_off > total) return ZO_E_FORMAT;
+    if (c0 > c1 || c1 > K) return ZO_E_ARG;
+
+    const uint8_t *len = blob + len_off;
+    if (zo_kraft_units(len) > (1u << ZO_MAX_LEN)) return ZO_E_FORMAT;
+    if (max_code_len(len) != L) return ZO_E_FORMAT;
+    if (get32(blob + H_R) != round_symbols(L)) return ZO_E_FORMAT;
+    uint16_t code[256];
+    int n_present = zo_canonical(len, code);
+    int pad = pad_symbol(len);
+    if ((uint32_t)n_present != get32(blob + H_NPRESENT) || (uint32_t)pad != get32(blob + H_PADSYM)) return ZO_E_FORMAT;
+
+    const uint8_t *sm = blob + sm_off;
+    uint8_t *e = (uint8_t *)malloc(C);
+    uint32_t *wbuf = (uint32_t *)malloc(stream_words_bound(W) * sizeof(uint32_t));
+    int rc = ZO_OK;
+    for (uint64_t c = c0; c < c1 && rc == ZO_OK; c++) {
+        uint64_t ent = get64(blob + table_off + 8 * c), nxt = get64(blob + table_off + 8 * (c + 1));
+        uint64_t at = ent & ~(uint64_t)15, end = nxt & ~(uint64_t)15;
+        unsigned mode = (unsigned)(ent & 15);
+        uint32_t cn = (uint32_t)((n - c * C) < C ? (n - c * C) : C);
+        if (at < e_off || end < at || end > total) { rc = ZO_E_FORMAT; break; }
+        if (c == 0 && at != e_off) { rc = ZO_E_FORMAT; break; }
+        const uint8_t *base = blob + at;
+        if (mode == ZO_MODE_RAW) {
+            if (end - at != round_up(cn, 16)) { rc = ZO_E_FORMAT; break; }
+            memcpy(e, base, cn);
+        } else if (mode == ZO_MODE_CODED) {
+            uint32_t S = (cn + W - 1) / W;
+            uint64_t head = 16 + round_up(4 * ((uint64_t)S + 1), 16);
+            if (end - at < head) { rc = ZO_E_FORMAT; break; }
+            if (get32(base) != cn || get32(base + 4) != S || get32(base + 8) != end - at || get32(base + 12) != 0) { rc = ZO_E_FORMAT; break; }
+            if (get32(base + 16) != head || get32(base + 16 + 4 * S) != end - at) { rc = ZO_E_FORMAT; break; }
+            for (uint32_t s = 0; s < S && rc == ZO_OK; s++) {
+                uint32_t o0 = get32(base + 16 + 4 * s), o1 = get32(base + 16 + 4 * (s + 1));
+                if (o0 % 16 || o1 % 16 || o1 < o0 || o1 > end - at) { rc = ZO_E_FORMAT; break; }
+                size_t nw = (o1 - o0) / 4;
+                if (nw > stream_words_bound(W)) { rc = ZO_E_FORMAT; break; }
+                for (size_t j = 0; j < nw; j++) wbuf[j] = get32(base + o0 + 4 * j);
+                uint32_t sn = (cn - s * W) < W ? (cn - s * W) : W;
+                rc = decode_stream(wbuf, nw, sn, len, code, L, pad, e + (size_t)s * W);
+            }
+        } else rc = ZO_E_FORMAT;
+        if (rc == ZO_OK) zo_merge(e, sm + c * C, cn, out + c * C);
+    }
+    if (rc == ZO_OK && c1 == K && get64(blob + table_off + 8 * K) > total) rc = ZO_E_FORMAT;
+    free(e); free(wbuf);
+    return rc;
+}
+
+int zo_decode(const uint8_t *blob, size_t size, uint16_t *out, size_t out_cap)
+{
+    if (size < ZO_HEADER_BYTES || get32(blob + H_MAGIC) != ZO_MAGIC) return ZO_E_FORMAT;
+    if (out_cap < get64(blob + H_NVALUES)) return ZO_E_SIZE;
+    return zo_decode_chunks(blob, size, 0, get32(blob + H_NCHUNKS), out);
+}
+
+/* Checks that the stored decode table is the one the code lengths define. */
+int zo_check_table(const uint8_t *blob, size_t size)
+{
+    if (size < 384 || get32(blob + H_MAGIC) != ZO_MAGIC) return ZO_E_FORMAT;
+    const uint8_t *len = blob + get64(blob + H_LEN_OFF);
+    int L = (int)get32(blob + H_L);
+    uint64_t lut_off = get64(blob + H_LUT_OFF);
+    if (L < 1 || L > ZO_MAX_LEN || lut_off + 2 * ((uint64_t)1 << L) > size) return ZO_E_FORMAT;
+    uint16_t code[256];
+    zo_canonical(len, code);
+    int pad = pad_symbol(len);
+    for (uint32_t x = 0; x < (1u << L); x++) {
+        /* walk the bits of x as the decoder would */
+        uint32_t acc = 0; int found = -1, l = 0;
+        while (found < 0 && l < L) {
+            acc = (acc << 1) | ((x >> l) & 1u); l++;
+            for (int s = 0; s < 256; s++) if (len[s] == l && code[s] == acc) { found = s; break; }
+        }
+        int sym = found >= 0 ? found : pad, sl = found >= 0 ? l : 1;
+        if (blob[lut_off + 2 * x] != sym || blob[lut_off + 2 * x + 1] != sl) return ZO_E_FORMAT;
+    }
+    return ZO_OK;
+}
