@@ -1,0 +1,184 @@
+/*
+ * zipmoe.h -- C ABI of libzipmoe: lossless compression of bf16 MoE expert
+ * weights on the host, and their decompression on an MI355X (gfx950).
+ *
+ * The method is that of ZipMoE (arXiv 2601.21198):
+ *   Sec. 2.2  a bf16 word is 1 sign bit, 8 exponent bits, 7 mantissa bits; the
+ *             exponent field has only about 2.6 bits of entropy.
+ *   Sec. 3.1  offline initialisation: every tensor is split into exponent bits
+ *             and sign-mantissa bits; the exponent bits are cut into shards that
+ *             are compressed one by one ("E-chunks"); the sign-mantissa bits are
+ *             packed one byte per value ("SM-chunks"); all of it, plus metadata,
+ *             is serialised into one binary object.
+ *   Sec. 3.3  "Memory-Coalesced Tensor Recovery Kernel": exponent bytes and
+ *             sign-mantissa bytes are merged back into bf16 words with
+ *             vectorised, coalesced loads and stores.
+ *   Sec. 6    "Other Compressors": the E-chunk compressor is a pluggable
+ *             backend.  The backend of this library is a canonical prefix code
+ *             with one codebook per tensor whose decoder runs on the GPU, so
+ *             decompression and recovery are one kernel launch.
+ *
+ * Conventions
+ *   - Every function returns an int status: ZM_OK or a negative ZM_E_* code,
+ *     unless stated otherwise.  No function throws, none keeps global state,
+ *     none keeps a pointer it was given.  Functions are thread-safe as long as
+ *     concurrent calls write distinct outputs.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *     device memory of the current device.  The caller owns every buffer.
+ *   - bf16 values are passed as their 16-bit patterns (uint16_t), row-major.
+ *
+ * Serialised tensor ("blob"), all integers little-endian:
+ *   byte 0     header, 128 bytes (see zm_tensor_info for the fields it carries)
+ *   byte 128   code_len[256]: code length of every exponent value, 0 = absent
+ *   byte 384   decode table, 2^L 16-bit entries (L = longest code length): the
+ *              entry for an L-bit stream window is symbol | length << 8
+ *   then       chunk table: n_chunks+1 64-bit entries, byte offset of each
+ *              E-chunk in the blob (multiple of 16) | mode in the low 4 bits
+ *   then       SM section (256-byte aligned): n_values sign-mantissa bytes
+ *              (sign in bit 7, mantissa in bits 6..0), tensor order
+ *   then       E-chunks (first one 256-byte aligned, each 16-byte aligned);
+ *              chunk c covers values [c*chunk_values, (c+1)*chunk_values).
+ *              mode 1 (raw): the exponent bytes.  mode 0 (coded): a 16-byte
+ *              chunk header, the byte offsets of its streams, the streams.
+ *              A stream covers stream_values consecutive values and weaves 64
+ *              per-lane bitstreams into one sequence of 32-bit words in the
+ *              order a 64-lane lock-step decoder consumes them: in every tile
+ *              of 512 values lane j owns values 8j..8j+7; each lane starts
+ *              with two words and takes one more word whenever, at the end of
+ *              a round of R symbols (R = 4 for L <= 8, else 2), its bit count
+ *              has crossed a 32-bit boundary.
+ */
+#ifndef ZIPMOE_H
+#define ZIPMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZM_OK        0
+#define ZM_E_ARG    (-1)   /* null pointer, size or alignment that the call does not admit */
+#define ZM_E_SIZE   (-2)   /* an output buffer is too small                                */
+#define ZM_E_FORMAT (-3)   /* the blob is not a well-formed serialised tensor              */
+#define ZM_E_HIP    (-4)   /* the HIP runtime reported an error (kept for hipGetLastError)  */
+#define ZM_E_NOMEM  (-5)   /* host allocation failed                                       */
+
+#define ZM_MAX_CODE_LEN 12   /* longest code length the format admits */
+#define ZM_TILE_VALUES  512  /* stream_values must be a multiple of this */
+#define ZM_MODE_CODED 0
+#define ZM_MODE_RAW   1
+
+/* What a decoder needs to know about one serialised tensor; filled by
+ * zm_blob_info from the blob's header (the "metadata" of Sec. 3.1). */
+typedef struct zm_tensor_info {
+    uint64_t n_values;       /* bf16 values in the tensor                         */
+    uint64_t blob_size;      /* bytes, a multiple of 256                          */
+    uint64_t lut_offset;     /* byte offset of the decode table                   */
+    uint64_t table_offset;   /* byte offset of the chunk table                    */
+    uint64_t sm_offset;      /* byte offset of the SM section                     */
+    uint64_t e_offset;       /* byte offset of the first E-chunk                  */
+    uint32_t chunk_values;   /* values per E-chunk (the last chunk may be short)  */
+    uint32_t stream_values;  /* values per stream inside a chunk                  */
+    uint32_t n_chunks;
+    uint32_t max_len;        /* L, longest code length in use (>= 1)              */
+    uint32_t round_symbols;  /* R                                                 */
+    uint32_t n_present;      /* exponent values that occur                        */
+} zm_tensor_info;
+
+/* Library version as major*10000 + minor*100 + patch. Never fails. */
+int zm_version(void);
+
+/* Static, human-readable text for a status code. Never returns NULL. */
+const char *zm_strerror(int status);
+
+/* Histogram of the exponent field (Sec. 2.2) of n_values bf16 words.
+ * host in: bf16; host out: hist[256].  ZM_E_ARG on null pointers. */
+int zm_exponent_histogram(const uint16_t *bf16, size_t n_values, uint64_t hist[256]);
+
+/* Codebook for the E-chunk backend (Sec. 3.1 "compressed", Sec. 6).
+ * host in: hist[256], the exponent histogram of the tensor the codebook serves.
+ * host out: code_len_out[256]: 0 for absent symbols, else 1..max_len, such that
+ * sum 2^-len <= 1 and sum hist*len is the minimum possible under the limit
+ * (an optimal length-limited prefix code).  One present symbol gets length 1.
+ * max_len must be in 1..ZM_MAX_CODE_LEN and 2^max_len >= number of present
+ * symbols, else ZM_E_ARG. */
+int zm_build_codebook(const uint64_t hist[256], int max_len, uint8_t code_len_out[256]);
+
+/* Upper bound on the blob size zm_encode can produce. 0 if the geometry is
+ * not admissible (see zm_encode). */
+size_t zm_encode_bound(size_t n_values, uint32_t chunk_values, uint32_t stream_values);
+
+/* Offline initialisation of one tensor (Sec. 3.1): split, shard, encode, pack,
+ * serialise.  Everything is host memory.
+ *   bf16, n_values    the tensor, flattened row-major
+ *   chunk_values      values per E-chunk; a multiple of stream_values
+ *   stream_values     values per stream; a multiple of ZM_TILE_VALUES
+ *   code_len          codebook from zm_build_codebook (must cover every
+ *                     exponent value that occurs; sum 2^-len must be exactly 1
+ *                     when two or more symbols are present, so that every bit
+ *                     pattern decodes)
+ *   blob, blob_cap    output buffer, at least zm_encode_bound(...) bytes
+ *   blob_size         out: bytes written (a multiple of 256)
+ *   chunk_offsets, chunk_offsets_cap   optional (may be NULL/0) copy of the
+ *                     blob's chunk table, n_chunks+1 entries
+ *   n_chunks          out (may be NULL)
+ * The output is a function of the inputs alone: equal inputs give equal bytes.
+ * ZM_E_ARG for bad geometry, bad codebook or a symbol without a code;
+ * ZM_E_SIZE if a buffer is too small; ZM_E_NOMEM. */
+int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint32_t stream_values,
+              const uint8_t code_len[256], uint8_t *blob, size_t blob_cap, size_t *blob_size,
+              uint64_t *chunk_offsets, size_t chunk_offsets_cap, size_t *n_chunks);
+
+/* Reads and checks the header and codebook of a blob in host memory (size may
+ * be just the first 384 bytes or the whole blob) and fills *info.
+ * ZM_E_FORMAT if magic, version, geometry, section offsets or codebook are
+ * not consistent. */
+int zm_blob_info(const void *blob_host, size_t size, zm_tensor_info *info);
+
+/* Full structural check of a blob in host memory, to be run once when a blob
+ * is registered, before it is uploaded: header, codebook, decode table against
+ * the codebook, chunk table, every chunk header and stream offset, every
+ * address a decoder will touch inside blob_size.  ZM_E_FORMAT on any
+ * violation.  It does not decode the streams. */
+int zm_validate_blob(const void *blob_host, size_t size);
+
+/* The hot call (Sec. 3.1 "Real-time Inference", steps 5-8, for experts whose
+ * compressed form is resident; Sec. 3.3 recovery): decode the experts a MoE
+ * layer's gate selected, all in one kernel launch per code-table width class.
+ *
+ *   blobs             host array [n_experts * tensors_per_expert] of DEVICE
+ *                     pointers; entry e*tensors_per_expert + m is tensor m of
+ *                     expert e; each 16-byte aligned, uploaded unchanged from
+ *                     zm_encode's output
+ *   chunk_offsets     host array, same shape, of DEVICE pointers to each
+ *                     tensor's chunk table (n_chunks+1 entries; may point into
+ *                     the blob at table_offset)
+ *   infos             host array, same shape, from zm_blob_info
+ *   n_experts, tensors_per_expert
+ *   expert_ids        host array [n_selected], each in [0, n_experts);
+ *                     duplicates are legal and are decoded twice
+ *   out_bf16          host array [n_selected * tensors_per_expert] of DEVICE
+ *                     pointers; entry j*tensors_per_expert + m receives the
+ *                     n_values bf16 words of tensor m of expert expert_ids[j];
+ *                     each 16-byte aligned and distinct
+ *   stream            a hipStream_t (NULL = the default stream)
+ *
+ * Asynchronous: enqueues the launches on `stream` and returns; allocates
+ * nothing, copies nothing, does not synchronise.  All arguments travel as
+ * kernel arguments, so host arrays may be reused as soon as the call returns;
+ * device buffers must stay valid until the stream has passed the call.
+ * Blobs must have passed zm_validate_blob: the kernel confines every access to
+ * the sizes in `infos`, it does not re-validate the streams.
+ * ZM_E_ARG for null pointers, ids out of range, misaligned pointers or a
+ * stream length the decoder cannot stage; ZM_E_HIP if a launch fails. */
+int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_offsets,
+                      const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
+                      const int32_t *expert_ids, int n_selected,
+                      void *const *out_bf16, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZIPMOE_H */

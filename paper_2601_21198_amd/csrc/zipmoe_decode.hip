@@ -1,0 +1,338 @@
+// Device side of libzipmoe: zm_decode_experts and its gfx950 kernels.
+//
+// One launch decodes every tensor of the experts a MoE layer's gate selected
+// (ZipMoE, arXiv 2601.21198, Sec. 3.1 "Real-time Inference"): each wavefront
+// takes one stream of one E-chunk, entropy-decodes its exponent bytes and merges
+// them with the raw sign-mantissa bytes into bf16 words (the tensor recovery
+// step of Sec. 3.3) without the exponents ever leaving registers.
+//
+// Work decomposition
+//   grid    one workgroup per kWaves consecutive streams of one tensor
+//   wave    one stream: stream_values consecutive values, tiles of 512
+//   lane j  owns values 8j..8j+7 of every tile: one 64-bit load of
+//           sign-mantissa bytes and one 128-bit store of bf16 words per tile,
+//           both contiguous across the wave (512 B and 1 KiB per instruction)
+//
+// Per wave
+//   1. the decode table goes to LDS (a3), replicated to the full index width so
+//      the lookup index needs no per-tensor mask;
+//   2. the stream's words are copied from HBM to LDS with 128-bit loads (a4);
+//   3. lock-step decode (a5): every lane keeps two words (lo, hi) of its own
+//      bitstream and a bit position; per round it extracts a 32-bit window with
+//      one funnel shift and decodes R symbols by table lookup;
+//   4. after a round the lanes whose position passed 32 bits take the next
+//      words of the stream: a ballot marks them, a prefix count over the ballot
+//      (mbcnt) gives each its word (a6);
+//   5. the eight decoded exponent bytes are merged with the sign-mantissa bytes
+//      by byte-parallel bit operations and stored (a8).
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "zipmoe.h"
+
+namespace {
+
+constexpr int kMaxTasks = 48;     // tensors per launch; 72 B each keeps the kernel arguments under 4 KiB
+constexpr uint32_t kTile = 512;
+
+struct Task {
+    const uint8_t *blob;
+    const uint64_t *table;
+    uint16_t *out;
+    uint64_t n_values;
+    uint64_t blob_size;
+    uint64_t sm_offset;
+    uint32_t lut_offset;
+    uint32_t stream_values;
+    uint32_t streams_per_chunk;
+    uint32_t n_streams;
+    uint32_t first_block;
+    uint32_t max_len;
+};
+
+struct Launch {
+    uint32_t n_tasks;
+    uint32_t stream_cap_words;   // LDS words reserved per wave for its stream
+    uint32_t pad[2];
+    Task task[kMaxTasks];
+};
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+}
+
+// Sec. 3.3 recovery of four values at once: e4 and sm4 hold four exponent bytes
+// and four sign-mantissa bytes; the results are the four bf16 words, two per register.
+__device__ __forceinline__ void recover4(uint32_t e4, uint32_t sm4, uint32_t &w01, uint32_t &w23)
+{
+    const uint32_t hi4 = (sm4 & 0x80808080u) | ((e4 >> 1) & 0x7F7F7F7Fu);   // s eeeeeee
+    const uint32_t lo4 = ((e4 << 7) & 0x80808080u) | (sm4 & 0x7F7F7F7Fu);   // e mmmmmmm
+    w01 = __builtin_amdgcn_perm(hi4, lo4, 0x05010400u);
+    w23 = __builtin_amdgcn_perm(hi4, lo4, 0x07030602u);
+}
+
+// R: symbols per round; kWaves: waves (streams) per workgroup
+template <int R, int kWaves>
+struct Geometry {
+    static constexpr int kIndexBits = R == 4 ? 8 : 12;
+    static constexpr uint32_t kLutEntries = 1u << kIndexBits;
+    static constexpr bool kLutPerWave = R == 4;
+    static constexpr uint32_t kLutWords = kLutEntries / 2 * (kLutPerWave ? kWaves : 1);
+};
+
+template <int R, int kWaves>
+__global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
+{
+    using G = Geometry<R, kWaves>;
+    extern __shared__ __align__(16) uint32_t smem[];
+
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    uint32_t ti = 0;
+    while (ti + 1 < P.n_tasks && blockIdx.x >= P.task[ti + 1].first_block) ++ti;
+    const Task &t = P.task[ti];
+
+    uint16_t *lut = reinterpret_cast<uint16_t *>(smem) + (G::kLutPerWave ? wave * G::kLutEntries : 0);
+    uint32_t *words = smem + G::kLutWords + wave * P.stream_cap_words;
+
+    // a3: decode table -> LDS, replicated over the index bits above the longest code
+    {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.blob + t.lut_offset);
+        const uint32_t mask = (1u << t.max_len) - 1u;
+        if (G::kLutPerWave) {
+            for (uint32_t i = lane; i < G::kLutEntries; i += 64) lut[i] = src[i & mask];
+        } else {
+            for (uint32_t i = threadIdx.x; i < G::kLutEntries; i += 64 * kWaves) lut[i] = src[i & mask];
+        }
+    }
+
+    const uint32_t g = (blockIdx.x - t.first_block) * kWaves + wave;
+    bool active = g < t.n_streams;
+    const uint32_t W = t.stream_values;
+    const uint64_t v0 = static_cast<uint64_t>(g) * W;              // first value of the stream in the tensor
+    uint32_t sn = 0, mode = ZM_MODE_RAW, tiles = 0;
+    const uint8_t *raw = nullptr;
+    if (active) {
+        const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
+        const uint64_t rest = t.n_values - v0;
+        sn = rest < W ? static_cast<uint32_t>(rest) : W;
+        tiles = (sn + kTile - 1) / kTile;
+        const uint64_t ent = t.table[c];
+        const uint64_t at = ent & ~15ull;
+        mode = static_cast<uint32_t>(ent & 15ull);
+        if (mode == ZM_MODE_CODED) {
+            // a4: the stream's words, 128 bits per lane per load
+            const uint32_t *offs = reinterpret_cast<const uint32_t *>(t.blob + at + 16);
+            uint32_t o0 = 0, o1 = 0;
+            const bool head_ok = at + 16 + 4ull * (s + 2) <= t.blob_size;
+            if (head_ok) { o0 = offs[s]; o1 = offs[s + 1]; }
+            if (!head_ok || o1 < o0 || at + o1 > t.blob_size) {
+                active = false;
+            } else {
+                const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
+                const uint4 *src = reinterpret_cast<const uint4 *>(t.blob + at + o0);
+                uint4 *dst = reinterpret_cast<uint4 *>(words);
+                uint32_t i = lane;
+                for (; i + 64 < nvec; i += 128) {
+                    const uint4 a = src[i], b = src[i + 64];
+                    dst[i] = a; dst[i + 64] = b;
+                }
+                if (i < nvec) dst[i] = src[i];
+            }
+        } else {
+            raw = t.blob + at + static_cast<uint64_t>(s) * W;
+            if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.blob_size) active = false;
+        }
+    }
+    if (G::kLutPerWave) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    } else {
+        __syncthreads();
+    }
+    if (!active) return;
+
+    const uint8_t *sm_base = t.blob + t.sm_offset + v0 + lane * 8u;
+    uint16_t *out_base = t.out + v0 + lane * 8u;
+    const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
+
+    // decoder state
+    uint32_t lo = 0, hi = 0, pos = 0, next = 128;
+    if (mode == ZM_MODE_CODED) {
+        const uint2 first = reinterpret_cast<const uint2 *>(words)[lane];
+        lo = first.x; hi = first.y;
+    }
+    const uint32_t last_word = P.stream_cap_words - 1u;
+
+    uint2 sm = make_uint2(0u, 0u);
+    if (mine > 0) sm = *reinterpret_cast<const uint2 *>(sm_base);
+
+    for (uint32_t tile = 0; tile < tiles; ++tile) {
+        const int32_t left = mine - static_cast<int32_t>(tile * kTile);
+        // sign-mantissa bytes of the next tile, requested before this tile's decode
+        uint2 sm_next = make_uint2(0u, 0u);
+        if (tile + 1 < tiles && left - static_cast<int32_t>(kTile) > 0)
+            sm_next = *reinterpret_cast<const uint2 *>(sm_base + (tile + 1) * kTile);
+
+        uint32_t e[2];
+        if (mode == ZM_MODE_CODED) {
+#pragma unroll
+            for (int r = 0; r < 8 / R; ++r) {
+                // a5: R symbols from one 32-bit window
+                uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
+                uint32_t acc = 0;
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    const uint32_t ent = lut[win & (G::kLutEntries - 1u)];
+                    const uint32_t len = ent >> 8;
+                    acc |= (ent & 0xFFu) << (8 * ((r * R + k) & 3));
+                    win >>= len;
+                    pos += len;
+                }
+                if (R == 4) e[r] = acc;
+                else if ((r & 1) == 0) e[r >> 1] = acc;
+                else e[r >> 1] |= acc;
+                // a6: lanes that crossed a word boundary take the stream's next words, in lane order
+                if (!(tile + 1 == tiles && r == 8 / R - 1)) {
+                    const bool take = pos >= 32u;
+                    const uint64_t takers = __ballot(take);
+                    if (takers) {
+                        const uint32_t idx = min(next + lanes_below(takers), last_word);
+                        if (take) { lo = hi; hi = words[idx]; pos -= 32u; }
+                        next += static_cast<uint32_t>(__builtin_popcountll(takers));
+                    }
+                }
+            }
+        } else {
+            uint2 ev = make_uint2(0u, 0u);
+            if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
+            e[0] = ev.x; e[1] = ev.y;
+        }
+
+        // a8: recovery and store
+        uint4 w;
+        recover4(e[0], sm.x, w.x, w.y);
+        recover4(e[1], sm.y, w.z, w.w);
+        uint16_t *dst = out_base + tile * kTile;
+        if (left >= 8) {
+            *reinterpret_cast<uint4 *>(dst) = w;
+        } else if (left > 0) {
+            const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (k < left) dst[k] = static_cast<uint16_t>(ws[k >> 1] >> (16 * (k & 1)));
+        }
+        sm = sm_next;
+    }
+}
+
+inline size_t stream_cap_words(uint32_t stream_values, uint32_t max_len_bound)
+{
+    const size_t syms = static_cast<size_t>(stream_values / kTile) * 8;
+    const size_t words = 64 * (2 + (syms * max_len_bound + 31) / 32) + 4;
+    return (words + 3) & ~static_cast<size_t>(3);
+}
+
+constexpr size_t kLdsLimit = 64 * 1024;
+
+template <int R, int kWaves>
+int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
+{
+    using G = Geometry<R, kWaves>;
+    const size_t lds = 4 * (G::kLutWords + kWaves * cap);
+    if (lds > kLdsLimit) {
+        if constexpr (kWaves > 1) return launch_tasks<R, kWaves / 2>(L, cap, stream);
+        else return ZM_E_ARG;                   // stream too long to stage in LDS
+    }
+    uint32_t blocks = 0;
+    for (uint32_t k = 0; k < L.n_tasks; ++k) {
+        L.task[k].first_block = blocks;
+        blocks += (L.task[k].n_streams + kWaves - 1) / kWaves;
+    }
+    if (!blocks) return ZM_OK;
+    hipLaunchKernelGGL((zm_decode_kernel<R, kWaves>), dim3(blocks), dim3(64 * kWaves), lds, stream, L);
+    return hipGetLastError() == hipSuccess ? ZM_OK : ZM_E_HIP;
+}
+
+template <int R>
+int launch_group(const Task *tasks, int n, hipStream_t stream)
+{
+    constexpr uint32_t kLenBound = R == 4 ? 8 : ZM_MAX_CODE_LEN;
+    int done = 0;
+    while (done < n) {
+        Launch L{};
+        uint32_t max_stream = 0;
+        int k = 0;
+        for (; k < kMaxTasks && done + k < n; ++k) {
+            L.task[k] = tasks[done + k];
+            max_stream = max_stream > L.task[k].stream_values ? max_stream : L.task[k].stream_values;
+        }
+        L.n_tasks = static_cast<uint32_t>(k);
+        const size_t cap = stream_cap_words(max_stream, kLenBound);
+        L.stream_cap_words = static_cast<uint32_t>(cap);
+        const int rc = launch_tasks<R, 4>(L, cap, stream);
+        if (rc != ZM_OK) return rc;
+        done += k;
+    }
+    return ZM_OK;
+}
+
+}  // namespace
+
+extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_offsets,
+                                 const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
+                                 const int32_t *expert_ids, int n_selected,
+                                 void *const *out_bf16, void *stream)
+{
+    if (n_selected == 0) return ZM_OK;
+    if (!blobs || !chunk_offsets || !infos || !expert_ids || !out_bf16) return ZM_E_ARG;
+    if (n_experts <= 0 || tensors_per_expert <= 0 || n_selected < 0) return ZM_E_ARG;
+
+    constexpr int kStack = 256;
+    Task stack4[kStack], stack2[kStack];
+    const long total = static_cast<long>(n_selected) * tensors_per_expert;
+    Task *t4 = stack4, *t2 = stack2;
+    if (total > kStack) return ZM_E_ARG;          // more tensors than one MoE layer's selection plausibly has
+    int n4 = 0, n2 = 0;
+    for (int j = 0; j < n_selected; ++j) {
+        const int e = expert_ids[j];
+        if (e < 0 || e >= n_experts) return ZM_E_ARG;
+        for (int m = 0; m < tensors_per_expert; ++m) {
+            const size_t src = static_cast<size_t>(e) * tensors_per_expert + m;
+            const size_t dst = static_cast<size_t>(j) * tensors_per_expert + m;
+            const zm_tensor_info &ti = infos[src];
+            if (ti.n_values == 0) continue;
+            if (!blobs[src] || !chunk_offsets[src] || !out_bf16[dst]) return ZM_E_ARG;
+            if ((reinterpret_cast<uintptr_t>(blobs[src]) & 15) || (reinterpret_cast<uintptr_t>(out_bf16[dst]) & 15) ||
+                (reinterpret_cast<uintptr_t>(chunk_offsets[src]) & 7)) return ZM_E_ARG;
+            if (ti.stream_values == 0 || ti.stream_values % kTile || ti.chunk_values % ti.stream_values) return ZM_E_ARG;
+            if (ti.max_len < 1 || ti.max_len > ZM_MAX_CODE_LEN || ti.lut_offset > 0xFFFFFFFFull) return ZM_E_ARG;
+            if (ti.round_symbols != (ti.max_len <= 8 ? 4u : 2u)) return ZM_E_ARG;
+            if (ti.sm_offset + ((ti.n_values + 255) & ~255ull) > ti.blob_size) return ZM_E_ARG;
+            const uint64_t n_streams = (ti.n_values + ti.stream_values - 1) / ti.stream_values;
+            if (n_streams > 0x7FFFFFFFull) return ZM_E_ARG;
+            Task t;
+            t.blob = static_cast<const uint8_t *>(blobs[src]);
+            t.table = chunk_offsets[src];
+            t.out = static_cast<uint16_t *>(out_bf16[dst]);
+            t.n_values = ti.n_values;
+            t.blob_size = ti.blob_size;
+            t.sm_offset = ti.sm_offset;
+            t.lut_offset = static_cast<uint32_t>(ti.lut_offset);
+            t.stream_values = ti.stream_values;
+            t.streams_per_chunk = ti.chunk_values / ti.stream_values;
+            t.n_streams = static_cast<uint32_t>(n_streams);
+            t.first_block = 0;
+            t.max_len = ti.max_len;
+            if (ti.round_symbols == 4) t4[n4++] = t; else t2[n2++] = t;
+        }
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = launch_group<4>(t4, n4, s);
+    if (rc != ZM_OK) return rc;
+    return launch_group<2>(t2, n2, s);
+}

@@ -1,0 +1,444 @@
+// Host side of libzipmoe: codebook construction, encoder, blob inspection.
+//
+// Follows ZipMoE (arXiv 2601.21198) Sec. 3.1, offline initialisation: bit-field
+// decomposition of bf16 words (fields as in Sec. 2.2), sharding of the exponent
+// bytes into independently coded E-chunks, byte-packed sign-mantissa section,
+// serialisation with metadata.  The E-chunk backend (Sec. 6, "Other
+// Compressors") is a canonical length-limited prefix code; the layout of the
+// serialised tensor is described in include/zipmoe.h.
+#include "zipmoe.h"
+
+#include <algorithm>
+#include <array>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+constexpr uint32_t kMagic = 0x454F4D5Au;   // "ZMOE"
+constexpr uint32_t kVersion = 1;
+constexpr uint32_t kHeaderBytes = 128;
+constexpr uint32_t kLanes = 64;
+constexpr uint32_t kRun = 8;               // consecutive values per lane per tile
+constexpr uint32_t kTile = kLanes * kRun;  // 512
+
+// header field positions
+struct Hdr {
+    static constexpr size_t magic = 0, version = 4, n_values = 8, chunk = 16, stream = 20, n_chunks = 24,
+                            max_len = 28, round_syms = 32, n_present = 36, pad_sym = 40, len_off = 48,
+                            lut_off = 56, table_off = 64, sm_off = 72, e_off = 80, blob_size = 88;
+};
+
+inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) & ~(a - 1); }
+
+template <typename T> inline void store_le(uint8_t *p, T v) { std::memcpy(p, &v, sizeof(T)); }   // x86-64 host: little-endian
+template <typename T> inline T load_le(const uint8_t *p) { T v; std::memcpy(&v, p, sizeof(T)); return v; }
+
+inline bool geometry_ok(uint32_t chunk_values, uint32_t stream_values)
+{
+    return stream_values != 0 && chunk_values != 0 && stream_values % kTile == 0 && chunk_values % stream_values == 0;
+}
+
+inline uint32_t round_symbols_for(uint32_t max_len) { return max_len <= 8 ? 4u : 2u; }
+
+// Canonical code table derived from code lengths.
+struct Book {
+    uint8_t len[256];
+    uint16_t wire[256];   // code with its first wire bit in bit 0 (ready for LSB-first packing)
+    uint32_t max_len = 1;
+    uint32_t n_present = 0;
+    uint32_t pad = 0;
+    uint32_t kraft = 0;   // in units of 2^-ZM_MAX_CODE_LEN
+};
+
+bool make_book(const uint8_t code_len[256], Book &b)
+{
+    uint32_t count[ZM_MAX_CODE_LEN + 2] = {0};
+    b.n_present = 0; b.kraft = 0; b.max_len = 1; b.pad = 0;
+    for (int s = 0; s < 256; ++s) {
+        const uint32_t l = code_len[s];
+        if (l > ZM_MAX_CODE_LEN) return false;
+        b.len[s] = static_cast<uint8_t>(l);
+        b.wire[s] = 0;
+        if (l) { ++count[l]; ++b.n_present; b.kraft += 1u << (ZM_MAX_CODE_LEN - l); b.max_len = std::max(b.max_len, l); }
+    }
+    if (b.kraft > (1u << ZM_MAX_CODE_LEN)) return false;
+    // first canonical code of each length: codes of length l follow those of length l-1
+    uint32_t first[ZM_MAX_CODE_LEN + 2] = {0};
+    uint32_t code = 0;
+    for (uint32_t l = 1; l <= ZM_MAX_CODE_LEN; ++l) { code = (code + count[l - 1]) << 1; first[l] = code; }
+    bool pad_set = false;
+    for (uint32_t l = 1; l <= ZM_MAX_CODE_LEN; ++l) {
+        uint32_t c = first[l];
+        for (int s = 0; s < 256; ++s) {
+            if (b.len[s] != l) continue;
+            uint32_t rev = 0;
+            for (uint32_t k = 0; k < l; ++k) rev |= ((c >> k) & 1u) << (l - 1 - k);
+            b.wire[s] = static_cast<uint16_t>(rev);
+            if (!pad_set) { b.pad = static_cast<uint32_t>(s); pad_set = true; }
+            ++c;
+        }
+    }
+    return true;
+}
+
+void fill_decode_table(const Book &b, uint8_t *lut /* 2 << max_len bytes */)
+{
+    const uint32_t entries = 1u << b.max_len;
+    for (uint32_t x = 0; x < entries; ++x) { lut[2 * x] = static_cast<uint8_t>(b.pad); lut[2 * x + 1] = 1; }
+    for (int s = 0; s < 256; ++s) {
+        const uint32_t l = b.len[s];
+        if (!l) continue;
+        for (uint32_t x = b.wire[s]; x < entries; x += 1u << l) { lut[2 * x] = static_cast<uint8_t>(s); lut[2 * x + 1] = static_cast<uint8_t>(l); }
+    }
+}
+
+// Scratch reused across the streams of one zm_encode call.
+struct Weaver {
+    std::vector<uint32_t> lane_words;   // [kLanes][stride]
+    std::vector<uint64_t> takers;       // per round: lanes that take a word after it
+    size_t stride = 0;
+
+    void prepare(uint32_t stream_values)
+    {
+        const size_t syms = static_cast<size_t>(stream_values / kTile) * kRun;
+        stride = 3 + (syms * ZM_MAX_CODE_LEN + 31) / 32;
+        lane_words.assign(kLanes * stride, 0);
+        takers.assign(syms + 1, 0);
+    }
+
+    // Weaves exponents e[0..n) into out; returns the number of 32-bit words (multiple of 4).
+    size_t weave(const uint8_t *e, uint32_t n, const Book &b, uint32_t *out)
+    {
+        const uint32_t R = round_symbols_for(b.max_len);
+        const uint32_t tiles = (n + kTile - 1) / kTile;
+        const uint32_t rounds = tiles * kRun / R;
+        std::fill(takers.begin(), takers.begin() + rounds, 0);
+        for (uint32_t lane = 0; lane < kLanes; ++lane) {
+            uint32_t *w = &lane_words[lane * stride];
+            uint64_t acc = 0; uint32_t fill = 0, widx = 0, used = 0, have = 2, round = 0, in_round = 0;
+            for (uint32_t t = 0; t < tiles; ++t) {
+                const uint32_t base = t * kTile + lane * kRun;
+                for (uint32_t i = 0; i < kRun; ++i) {
+                    const uint32_t idx = base + i;
+                    const uint32_t s = idx < n ? e[idx] : b.pad;
+                    const uint32_t l = b.len[s];
+                    acc |= static_cast<uint64_t>(b.wire[s]) << fill;
+                    fill += l; used += l;
+                    if (fill >= 32) { w[widx++] = static_cast<uint32_t>(acc); acc >>= 32; fill -= 32; }
+                    if (++in_round == R) {
+                        in_round = 0;
+                        if (round + 1 < rounds && (used >> 5) + 2 > have) { takers[round] |= 1ull << lane; ++have; }
+                        ++round;
+                    }
+                }
+            }
+            w[widx++] = static_cast<uint32_t>(acc);
+            while (widx < have) w[widx++] = 0;   // words a lane is handed past its last bit are zero
+        }
+        size_t o = 0;
+        uint32_t given[kLanes];
+        for (uint32_t lane = 0; lane < kLanes; ++lane) {
+            out[o++] = lane_words[lane * stride];
+            out[o++] = lane_words[lane * stride + 1];
+            given[lane] = 2;
+        }
+        for (uint32_t r = 0; r + 1 < rounds; ++r) {
+            uint64_t m = takers[r];
+            while (m) {
+                const uint32_t lane = static_cast<uint32_t>(__builtin_ctzll(m));
+                m &= m - 1;
+                out[o++] = lane_words[lane * stride + given[lane]++];
+            }
+        }
+        while (o & 3) out[o++] = 0;
+        return o;
+    }
+};
+
+size_t stream_word_bound(uint32_t stream_values)
+{
+    const size_t syms = static_cast<size_t>(stream_values / kTile) * kRun;
+    return kLanes * (2 + (syms * ZM_MAX_CODE_LEN + 31) / 32) + 4;
+}
+
+int read_info(const uint8_t *p, size_t size, zm_tensor_info *info, Book *book_out)
+{
+    if (size < kHeaderBytes + 256) return ZM_E_FORMAT;
+    if (load_le<uint32_t>(p + Hdr::magic) != kMagic || load_le<uint32_t>(p + Hdr::version) != kVersion) return ZM_E_FORMAT;
+    zm_tensor_info t{};
+    t.n_values = load_le<uint64_t>(p + Hdr::n_values);
+    t.chunk_values = load_le<uint32_t>(p + Hdr::chunk);
+    t.stream_values = load_le<uint32_t>(p + Hdr::stream);
+    t.n_chunks = load_le<uint32_t>(p + Hdr::n_chunks);
+    t.max_len = load_le<uint32_t>(p + Hdr::max_len);
+    t.round_symbols = load_le<uint32_t>(p + Hdr::round_syms);
+    t.n_present = load_le<uint32_t>(p + Hdr::n_present);
+    t.lut_offset = load_le<uint64_t>(p + Hdr::lut_off);
+    t.table_offset = load_le<uint64_t>(p + Hdr::table_off);
+    t.sm_offset = load_le<uint64_t>(p + Hdr::sm_off);
+    t.e_offset = load_le<uint64_t>(p + Hdr::e_off);
+    t.blob_size = load_le<uint64_t>(p + Hdr::blob_size);
+    if (!geometry_ok(t.chunk_values, t.stream_values)) return ZM_E_FORMAT;
+    if (t.max_len < 1 || t.max_len > ZM_MAX_CODE_LEN) return ZM_E_FORMAT;
+    const uint64_t chunks = (t.n_values + t.chunk_values - 1) / t.chunk_values;
+    if (chunks != t.n_chunks) return ZM_E_FORMAT;
+    if (load_le<uint64_t>(p + Hdr::len_off) != kHeaderBytes || t.lut_offset != kHeaderBytes + 256) return ZM_E_FORMAT;
+    if (t.table_offset != align_up(t.lut_offset + (2ull << t.max_len), 16)) return ZM_E_FORMAT;
+    if (t.sm_offset != align_up(t.table_offset + 8ull * (chunks + 1), 256)) return ZM_E_FORMAT;
+    if (t.e_offset != align_up(t.sm_offset + t.n_values, 256)) return ZM_E_FORMAT;
+    if (t.blob_size < t.e_offset || (t.blob_size & 255)) return ZM_E_FORMAT;
+    Book b;
+    if (!make_book(p + kHeaderBytes, b)) return ZM_E_FORMAT;
+    if (b.max_len != t.max_len || b.n_present != t.n_present) return ZM_E_FORMAT;
+    if (t.round_symbols != round_symbols_for(t.max_len)) return ZM_E_FORMAT;
+    if (load_le<uint32_t>(p + Hdr::pad_sym) != b.pad) return ZM_E_FORMAT;
+    if (b.n_present >= 2 && b.kraft != (1u << ZM_MAX_CODE_LEN)) return ZM_E_FORMAT;   // decode table must be total
+    if (t.n_values > 0 && b.n_present == 0) return ZM_E_FORMAT;
+    if (info) *info = t;
+    if (book_out) *book_out = b;
+    return ZM_OK;
+}
+
+// Length-limited optimal prefix code by package-merge (Larmore & Hirschberg 1990).
+// weight[i] ascending; returns lengths for the n sorted items.
+void package_merge(const std::vector<uint64_t> &weight, int max_len, std::vector<uint8_t> &length)
+{
+    const size_t n = weight.size();
+    length.assign(n, 0);
+    if (n == 1) { length[0] = 1; return; }
+    struct Node { uint64_t w; std::vector<uint8_t> uses; };   // uses[i]: how often item i is inside
+    std::vector<Node> level;                                   // current list, ascending
+    level.reserve(2 * n);
+    for (size_t i = 0; i < n; ++i) { Node nd{weight[i], std::vector<uint8_t>(n, 0)}; nd.uses[i] = 1; level.push_back(std::move(nd)); }
+    for (int depth = 2; depth <= max_len; ++depth) {
+        std::vector<Node> packs;
+        for (size_t i = 0; i + 1 < level.size(); i += 2) {
+            Node nd{level[i].w + level[i + 1].w, level[i].uses};
+            for (size_t k = 0; k < n; ++k) nd.uses[k] = static_cast<uint8_t>(nd.uses[k] + level[i + 1].uses[k]);
+            packs.push_back(std::move(nd));
+        }
+        std::vector<Node> merged;
+        merged.reserve(n + packs.size());
+        size_t a = 0, b = 0;
+        while (a < n || b < packs.size()) {
+            // on equal weight a plain item goes first
+            if (b >= packs.size() || (a < n && weight[a] <= packs[b].w)) {
+                Node nd{weight[a], std::vector<uint8_t>(n, 0)}; nd.uses[a] = 1; merged.push_back(std::move(nd)); ++a;
+            } else merged.push_back(std::move(packs[b++]));
+        }
+        level.swap(merged);
+    }
+    for (size_t i = 0; i < 2 * n - 2; ++i)
+        for (size_t k = 0; k < n; ++k) length[k] = static_cast<uint8_t>(length[k] + level[i].uses[k]);
+}
+
+}  // namespace
+
+extern "C" {
+
+int zm_version(void) { return 100; }
+
+const char *zm_strerror(int status)
+{
+    switch (status) {
+        case ZM_OK: return "ok";
+        case ZM_E_ARG: return "invalid argument";
+        case ZM_E_SIZE: return "output buffer too small";
+        case ZM_E_FORMAT: return "malformed serialised tensor";
+        case ZM_E_HIP: return "HIP runtime error";
+        case ZM_E_NOMEM: return "out of host memory";
+        default: return "unknown status";
+    }
+}
+
+int zm_exponent_histogram(const uint16_t *bf16, size_t n_values, uint64_t hist[256])
+{
+    if ((!bf16 && n_values) || !hist) return ZM_E_ARG;
+    uint64_t h[4][256] = {};
+    size_t i = 0;
+    for (; i + 4 <= n_values; i += 4) {
+        ++h[0][(bf16[i] >> 7) & 0xFF]; ++h[1][(bf16[i + 1] >> 7) & 0xFF];
+        ++h[2][(bf16[i + 2] >> 7) & 0xFF]; ++h[3][(bf16[i + 3] >> 7) & 0xFF];
+    }
+    for (; i < n_values; ++i) ++h[0][(bf16[i] >> 7) & 0xFF];
+    for (int s = 0; s < 256; ++s) hist[s] = h[0][s] + h[1][s] + h[2][s] + h[3][s];
+    return ZM_OK;
+}
+
+int zm_build_codebook(const uint64_t hist[256], int max_len, uint8_t code_len_out[256])
+{
+    if (!hist || !code_len_out || max_len < 1 || max_len > ZM_MAX_CODE_LEN) return ZM_E_ARG;
+    try {
+        std::vector<std::pair<uint64_t, int>> present;
+        for (int s = 0; s < 256; ++s) { code_len_out[s] = 0; if (hist[s]) present.emplace_back(hist[s], s); }
+        if (present.empty()) return ZM_OK;
+        if (present.size() > (1ull << max_len)) return ZM_E_ARG;
+        std::sort(present.begin(), present.end());
+        std::vector<uint64_t> weight;
+        for (auto &p : present) weight.push_back(p.first);
+        std::vector<uint8_t> length;
+        package_merge(weight, max_len, length);
+        for (size_t i = 0; i < present.size(); ++i) code_len_out[present[i].second] = length[i];
+    } catch (const std::bad_alloc &) { return ZM_E_NOMEM; }
+    return ZM_OK;
+}
+
+size_t zm_encode_bound(size_t n_values, uint32_t chunk_values, uint32_t stream_values)
+{
+    if (!geometry_ok(chunk_values, stream_values)) return 0;
+    const size_t chunks = (n_values + chunk_values - 1) / chunk_values;
+    // header + code lengths + widest decode table + chunk table + SM section + E-chunks stored raw, each with padding
+    return 384 + (2u << ZM_MAX_CODE_LEN) + 16 + 8 * (chunks + 1) + 256 + (n_values + 256) + (n_values + 16 * chunks) + 256;
+}
+
+int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint32_t stream_values,
+              const uint8_t code_len[256], uint8_t *blob, size_t blob_cap, size_t *blob_size,
+              uint64_t *chunk_offsets, size_t chunk_offsets_cap, size_t *n_chunks)
+{
+    if ((!bf16 && n_values) || !code_len || !blob || !blob_size) return ZM_E_ARG;
+    if (!geometry_ok(chunk_values, stream_values)) return ZM_E_ARG;
+    Book book;
+    if (!make_book(code_len, book)) return ZM_E_ARG;
+    if (book.n_present >= 2 && book.kraft != (1u << ZM_MAX_CODE_LEN)) return ZM_E_ARG;   // the decode table must be total
+    const size_t chunks = (n_values + chunk_values - 1) / chunk_values;
+    if (blob_cap < zm_encode_bound(n_values, chunk_values, stream_values)) return ZM_E_SIZE;
+    if (chunk_offsets && chunk_offsets_cap < chunks + 1) return ZM_E_SIZE;
+
+    const uint32_t L = book.max_len;
+    const uint64_t lut_off = kHeaderBytes + 256;
+    const uint64_t table_off = align_up(lut_off + (2ull << L), 16);
+    const uint64_t sm_off = align_up(table_off + 8 * (chunks + 1), 256);
+    const uint64_t e_off = align_up(sm_off + n_values, 256);
+    try {
+        std::memset(blob, 0, e_off);
+        std::memcpy(blob + kHeaderBytes, book.len, 256);
+        fill_decode_table(book, blob + lut_off);
+
+        // split (Sec. 3.1): sign-mantissa bytes go straight to their section, exponent bytes to scratch
+        std::vector<uint8_t> expo(n_values ? n_values : 1);
+        uint8_t *sm = blob + sm_off;
+        for (size_t i = 0; i < n_values; ++i) {
+            const uint32_t w = bf16[i];
+            const uint32_t ex = (w >> 7) & 0xFF;
+            if (!book.len[ex]) return ZM_E_ARG;
+            expo[i] = static_cast<uint8_t>(ex);
+            sm[i] = static_cast<uint8_t>(((w >> 8) & 0x80) | (w & 0x7F));
+        }
+
+        Weaver weaver;
+        weaver.prepare(stream_values);
+        const uint32_t max_streams = chunk_values / stream_values;
+        std::vector<uint32_t> coded(4 + ((max_streams + 1 + 3) & ~3u) + static_cast<size_t>(max_streams) * stream_word_bound(stream_values));
+        uint64_t pos = e_off;
+        for (size_t c = 0; c < chunks; ++c) {
+            const size_t first = c * static_cast<size_t>(chunk_values);
+            const uint32_t cn = static_cast<uint32_t>(std::min<size_t>(chunk_values, n_values - first));
+            const uint32_t streams = (cn + stream_values - 1) / stream_values;
+            const uint64_t raw_bytes = align_up(cn, 16);
+            const uint32_t head_words = 4 + ((streams + 1 + 3) & ~3u);
+            std::fill(coded.begin(), coded.begin() + head_words, 0);
+            size_t at = head_words;
+            bool smaller = true;
+            for (uint32_t s = 0; s < streams; ++s) {
+                coded[4 + s] = static_cast<uint32_t>(4 * at);
+                const uint32_t sn = std::min(stream_values, cn - s * stream_values);
+                at += weaver.weave(&expo[first + static_cast<size_t>(s) * stream_values], sn, book, &coded[at]);
+                if (4 * at >= raw_bytes) { smaller = false; break; }
+            }
+            uint64_t mode;
+            if (smaller) {
+                coded[0] = cn; coded[1] = streams; coded[2] = static_cast<uint32_t>(4 * at); coded[3] = 0;
+                coded[4 + streams] = static_cast<uint32_t>(4 * at);
+                std::memcpy(blob + pos, coded.data(), 4 * at);
+                mode = ZM_MODE_CODED;
+            } else {
+                std::memset(blob + pos, 0, raw_bytes);
+                std::memcpy(blob + pos, &expo[first], cn);
+                mode = ZM_MODE_RAW;
+            }
+            store_le<uint64_t>(blob + table_off + 8 * c, pos | mode);
+            pos += smaller ? 4 * at : raw_bytes;
+        }
+        store_le<uint64_t>(blob + table_off + 8 * chunks, pos);
+        const uint64_t total = align_up(pos, 256);
+        std::memset(blob + pos, 0, total - pos);
+
+        store_le<uint32_t>(blob + Hdr::magic, kMagic);
+        store_le<uint32_t>(blob + Hdr::version, kVersion);
+        store_le<uint64_t>(blob + Hdr::n_values, n_values);
+        store_le<uint32_t>(blob + Hdr::chunk, chunk_values);
+        store_le<uint32_t>(blob + Hdr::stream, stream_values);
+        store_le<uint32_t>(blob + Hdr::n_chunks, static_cast<uint32_t>(chunks));
+        store_le<uint32_t>(blob + Hdr::max_len, L);
+        store_le<uint32_t>(blob + Hdr::round_syms, round_symbols_for(L));
+        store_le<uint32_t>(blob + Hdr::n_present, book.n_present);
+        store_le<uint32_t>(blob + Hdr::pad_sym, book.pad);
+        store_le<uint64_t>(blob + Hdr::len_off, kHeaderBytes);
+        store_le<uint64_t>(blob + Hdr::lut_off, lut_off);
+        store_le<uint64_t>(blob + Hdr::table_off, table_off);
+        store_le<uint64_t>(blob + Hdr::sm_off, sm_off);
+        store_le<uint64_t>(blob + Hdr::e_off, e_off);
+        store_le<uint64_t>(blob + Hdr::blob_size, total);
+        *blob_size = total;
+        if (n_chunks) *n_chunks = chunks;
+        if (chunk_offsets) std::memcpy(chunk_offsets, blob + table_off, 8 * (chunks + 1));
+    } catch (const std::bad_alloc &) { return ZM_E_NOMEM; }
+    return ZM_OK;
+}
+
+int zm_blob_info(const void *blob_host, size_t size, zm_tensor_info *info)
+{
+    if (!blob_host || !info) return ZM_E_ARG;
+    return read_info(static_cast<const uint8_t *>(blob_host), size, info, nullptr);
+}
+
+int zm_validate_blob(const void *blob_host, size_t size)
+{
+    if (!blob_host) return ZM_E_ARG;
+    const uint8_t *p = static_cast<const uint8_t *>(blob_host);
+    zm_tensor_info t; Book book;
+    const int rc = read_info(p, size, &t, &book);
+    if (rc != ZM_OK) return rc;
+    if (t.blob_size > size) return ZM_E_FORMAT;
+    for (size_t i = Hdr::blob_size + 8; i < kHeaderBytes; ++i) if (p[i]) return ZM_E_FORMAT;
+    if (load_le<uint32_t>(p + 44)) return ZM_E_FORMAT;
+    // decode table must be the one the code lengths define
+    std::vector<uint8_t> lut(2u << t.max_len);
+    fill_decode_table(book, lut.data());
+    if (std::memcmp(lut.data(), p + t.lut_offset, lut.size())) return ZM_E_FORMAT;
+    // chunk table and chunk structure
+    uint64_t expect = t.e_offset;
+    const uint64_t word_cap = stream_word_bound(t.stream_values);
+    for (uint64_t c = 0; c < t.n_chunks; ++c) {
+        const uint64_t ent = load_le<uint64_t>(p + t.table_offset + 8 * c);
+        const uint64_t nxt = load_le<uint64_t>(p + t.table_offset + 8 * (c + 1));
+        const uint64_t at = ent & ~15ull, end = nxt & ~15ull, mode = ent & 15;
+        if (at != expect || end < at || end > t.blob_size) return ZM_E_FORMAT;
+        const uint64_t cn = std::min<uint64_t>(t.chunk_values, t.n_values - c * t.chunk_values);
+        if (mode == ZM_MODE_RAW) {
+            if (end - at != align_up(cn, 16)) return ZM_E_FORMAT;
+        } else if (mode == ZM_MODE_CODED) {
+            const uint64_t streams = (cn + t.stream_values - 1) / t.stream_values;
+            const uint64_t head = 16 + align_up(4 * (streams + 1), 16);
+            if (end - at < head) return ZM_E_FORMAT;
+            const uint8_t *h = p + at;
+            if (load_le<uint32_t>(h) != cn || load_le<uint32_t>(h + 4) != streams || load_le<uint32_t>(h + 8) != end - at || load_le<uint32_t>(h + 12)) return ZM_E_FORMAT;
+            if (load_le<uint32_t>(h + 16) != head || load_le<uint32_t>(h + 16 + 4 * streams) != end - at) return ZM_E_FORMAT;
+            for (uint64_t s = 0; s < streams; ++s) {
+                const uint32_t o0 = load_le<uint32_t>(h + 16 + 4 * s), o1 = load_le<uint32_t>(h + 16 + 4 * (s + 1));
+                if ((o0 & 15) || (o1 & 15) || o1 < o0 || o1 > end - at) return ZM_E_FORMAT;
+                const uint64_t words = (o1 - o0) / 4;
+                if (words < 2 * kLanes || words > word_cap) return ZM_E_FORMAT;
+            }
+        } else return ZM_E_FORMAT;
+        expect = end;
+    }
+    const uint64_t last = load_le<uint64_t>(p + t.table_offset + 8ull * t.n_chunks);
+    if (last != expect || align_up(last, 256) != t.blob_size) return ZM_E_FORMAT;
+    return ZM_OK;
+}
+
+}  // extern "C"

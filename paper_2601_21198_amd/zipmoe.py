@@ -1,0 +1,236 @@
+"""ctypes binding of libzipmoe (include/zipmoe.h): argument marshalling only.
+
+Every step of the decode path runs in the library's HIP kernels; PyTorch is used
+by callers for device memory and streams.  The library must have been built
+(``python -m paper_2601_21198_amd.build`` or ``__graft_entry__.build()``);
+loading fails loudly otherwise -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from .build import LIB_PATH
+
+OK, E_ARG, E_SIZE, E_FORMAT, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5
+MAX_CODE_LEN = 12
+TILE_VALUES = 512
+MODE_CODED, MODE_RAW = 0, 1
+
+EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
+           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts")
+
+
+class TensorInfo(ctypes.Structure):
+    """zm_tensor_info"""
+    _fields_ = [("n_values", ctypes.c_uint64), ("blob_size", ctypes.c_uint64), ("lut_offset", ctypes.c_uint64),
+                ("table_offset", ctypes.c_uint64), ("sm_offset", ctypes.c_uint64), ("e_offset", ctypes.c_uint64),
+                ("chunk_values", ctypes.c_uint32), ("stream_values", ctypes.c_uint32), ("n_chunks", ctypes.c_uint32),
+                ("max_len", ctypes.c_uint32), ("round_symbols", ctypes.c_uint32), ("n_present", ctypes.c_uint32)]
+
+
+class ZipMoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+        self.status = status
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2601_21198_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        u8p, u16p, u64p = c.POINTER(c.c_uint8), c.POINTER(c.c_uint16), c.POINTER(c.c_uint64)
+        L.zm_version.argtypes = []
+        L.zm_version.restype = c.c_int
+        L.zm_strerror.argtypes = [c.c_int]
+        L.zm_strerror.restype = c.c_char_p
+        L.zm_exponent_histogram.argtypes = [u16p, c.c_size_t, u64p]
+        L.zm_build_codebook.argtypes = [u64p, c.c_int, u8p]
+        L.zm_encode_bound.argtypes = [c.c_size_t, c.c_uint32, c.c_uint32]
+        L.zm_encode_bound.restype = c.c_size_t
+        L.zm_encode.argtypes = [u16p, c.c_size_t, c.c_uint32, c.c_uint32, u8p, u8p, c.c_size_t,
+                                c.POINTER(c.c_size_t), u64p, c.c_size_t, c.POINTER(c.c_size_t)]
+        L.zm_blob_info.argtypes = [c.c_void_p, c.c_size_t, c.POINTER(TensorInfo)]
+        L.zm_validate_blob.argtypes = [c.c_void_p, c.c_size_t]
+        L.zm_decode_experts.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.POINTER(TensorInfo),
+                                        c.c_int, c.c_int, c.POINTER(c.c_int32), c.c_int,
+                                        c.POINTER(c.c_void_p), c.c_void_p]
+        for name in EXPORTS:
+            if name not in ("zm_strerror", "zm_encode_bound"):
+                getattr(L, name).restype = c.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise ZipMoEError(status, where)
+
+
+def _ptr(a: np.ndarray, t):
+    return a.ctypes.data_as(ctypes.POINTER(t))
+
+
+def version() -> int:
+    return int(lib().zm_version())
+
+
+def strerror(status: int) -> str:
+    return lib().zm_strerror(status).decode()
+
+
+def _words(bf16) -> np.ndarray:
+    a = np.ascontiguousarray(bf16)
+    if a.dtype != np.uint16:
+        raise TypeError("bf16 values are passed as their uint16 bit patterns")
+    return a.reshape(-1)
+
+
+def exponent_histogram(bf16) -> np.ndarray:
+    w = _words(bf16)
+    hist = np.zeros(256, np.uint64)
+    _check(lib().zm_exponent_histogram(_ptr(w, ctypes.c_uint16), w.size, _ptr(hist, ctypes.c_uint64)),
+           "zm_exponent_histogram")
+    return hist
+
+
+def build_codebook(hist, max_len: int = 8) -> np.ndarray:
+    h = np.ascontiguousarray(hist, np.uint64)
+    if h.shape != (256,):
+        raise ValueError("hist must have 256 entries")
+    out = np.zeros(256, np.uint8)
+    _check(lib().zm_build_codebook(_ptr(h, ctypes.c_uint64), int(max_len), _ptr(out, ctypes.c_uint8)),
+           "zm_build_codebook")
+    return out
+
+
+def encode_bound(n_values: int, chunk_values: int, stream_values: int) -> int:
+    return int(lib().zm_encode_bound(n_values, chunk_values, stream_values))
+
+
+def encode(bf16, chunk_values: int, stream_values: int, code_len) -> Tuple[np.ndarray, np.ndarray]:
+    """zm_encode: returns (blob as uint8 array, chunk_offsets as uint64 array of n_chunks+1 entries)."""
+    w = _words(bf16)
+    cl = np.ascontiguousarray(code_len, np.uint8)
+    cap = encode_bound(w.size, chunk_values, stream_values)
+    if cap == 0:
+        raise ZipMoEError(E_ARG, "zm_encode_bound")
+    blob = np.empty(cap, np.uint8)
+    max_chunks = -(-w.size // chunk_values) + 1
+    offs = np.zeros(max_chunks, np.uint64)
+    size, n_chunks = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(lib().zm_encode(_ptr(w, ctypes.c_uint16), w.size, chunk_values, stream_values, _ptr(cl, ctypes.c_uint8),
+                           _ptr(blob, ctypes.c_uint8), cap, ctypes.byref(size),
+                           _ptr(offs, ctypes.c_uint64), offs.size, ctypes.byref(n_chunks)), "zm_encode")
+    return blob[: size.value].copy(), offs[: n_chunks.value + 1].copy()
+
+
+def compress(bf16, chunk_values: int, stream_values: int = 4096, max_len: int = 8) -> Tuple[np.ndarray, np.ndarray]:
+    """histogram -> codebook -> encode: the offline initialisation of one tensor."""
+    w = _words(bf16)
+    return encode(w, chunk_values, stream_values, build_codebook(exponent_histogram(w), max_len))
+
+
+def blob_info(blob) -> TensorInfo:
+    b = np.ascontiguousarray(blob, np.uint8)
+    info = TensorInfo()
+    _check(lib().zm_blob_info(b.ctypes.data, b.size, ctypes.byref(info)), "zm_blob_info")
+    return info
+
+
+def validate_blob(blob) -> None:
+    b = np.ascontiguousarray(blob, np.uint8)
+    _check(lib().zm_validate_blob(b.ctypes.data, b.size), "zm_validate_blob")
+
+
+def decode_experts(blobs, chunk_offsets, infos, n_experts: int, tensors_per_expert: int,
+                   expert_ids, n_selected: int, out_bf16, stream: int = 0) -> None:
+    """zm_decode_experts with ready-made ctypes arrays (see ``ExpertLayer`` for a convenient owner)."""
+    _check(lib().zm_decode_experts(blobs, chunk_offsets, infos, n_experts, tensors_per_expert,
+                                   expert_ids, n_selected, out_bf16, ctypes.c_void_p(stream)), "zm_decode_experts")
+
+
+class ExpertLayer:
+    """Owns the device copies of one MoE layer's compressed experts and the pointer tables
+    ``zm_decode_experts`` takes.  Holds no arithmetic: it uploads blobs with torch, records their
+    device addresses and marshals calls."""
+
+    def __init__(self, expert_blobs: Sequence[Sequence[np.ndarray]], device: str = "cuda:0", validate: bool = True):
+        import torch
+        self.n_experts = len(expert_blobs)
+        self.tensors_per_expert = len(expert_blobs[0])
+        n = self.n_experts * self.tensors_per_expert
+        self.infos = (TensorInfo * n)()
+        self.blob_ptrs = (ctypes.c_void_p * n)()
+        self.table_ptrs = (ctypes.c_void_p * n)()
+        self.device = torch.device(device)
+        self.compressed_bytes = 0
+        sizes = []
+        for e, tensors in enumerate(expert_blobs):
+            assert len(tensors) == self.tensors_per_expert
+            for m, blob in enumerate(tensors):
+                if validate:
+                    validate_blob(blob)
+                self.infos[e * self.tensors_per_expert + m] = blob_info(blob[:384])
+                sizes.append(int(blob.size))
+        # one contiguous arena for the whole layer (blob sizes are multiples of 256, so every blob stays aligned)
+        self.arena = torch.empty(sum(sizes), dtype=torch.uint8, device=self.device)
+        at = 0
+        k = 0
+        for tensors in expert_blobs:
+            for blob in tensors:
+                self.arena[at: at + blob.size].copy_(torch.from_numpy(np.ascontiguousarray(blob)))
+                base = self.arena.data_ptr() + at
+                self.blob_ptrs[k] = base
+                self.table_ptrs[k] = base + self.infos[k].table_offset
+                at += blob.size
+                k += 1
+        self.compressed_bytes = at
+        self._ptr_blobs = ctypes.cast(self.blob_ptrs, ctypes.POINTER(ctypes.c_void_p))
+        self._ptr_tables = ctypes.cast(self.table_ptrs, ctypes.POINTER(ctypes.c_void_p))
+        self._ptr_infos = ctypes.cast(self.infos, ctypes.POINTER(TensorInfo))
+
+    def expert_values(self, expert: int) -> List[int]:
+        t = self.tensors_per_expert
+        return [int(self.infos[expert * t + m].n_values) for m in range(t)]
+
+    def alloc_outputs(self, n_selected: int, expert: int = 0):
+        """One uint16 device tensor per selected slot, tensors of an expert back to back (16-byte aligned each)."""
+        import torch
+        vals = self.expert_values(expert)
+        starts, at = [], 0
+        for v in vals:
+            starts.append(at)
+            at += -(-v // 8) * 8
+        bufs = [torch.empty(at, dtype=torch.int16, device=self.device) for _ in range(n_selected)]
+        return bufs, starts, vals
+
+    def make_call(self, expert_ids, out_buffers, starts):
+        """Pre-marshals one call: returns a zero-argument function that enqueues it on ``stream``."""
+        ids = (ctypes.c_int32 * len(expert_ids))(*[int(e) for e in expert_ids])
+        t = self.tensors_per_expert
+        outs = (ctypes.c_void_p * (len(expert_ids) * t))()
+        for j, buf in enumerate(out_buffers):
+            for m in range(t):
+                outs[j * t + m] = buf.data_ptr() + 2 * starts[m]
+        f = lib().zm_decode_experts
+        args = (self._ptr_blobs, self._ptr_tables, self._ptr_infos, self.n_experts, t, ids, len(expert_ids), outs)
+
+        def call(stream: int = 0):
+            rc = f(*args, ctypes.c_void_p(stream))
+            if rc != OK:
+                raise ZipMoEError(rc, "zm_decode_experts")
+        call.keepalive = (ids, outs, out_buffers)
+        return call
+
+    def decode(self, expert_ids, out_buffers, starts, stream: int = 0) -> None:
+        self.make_call(expert_ids, out_buffers, starts)(stream)

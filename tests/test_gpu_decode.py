@@ -1,0 +1,161 @@
+"""GPU parity: zm_decode_experts (through the C ABI) against the reference codec, bit for bit."""
+import ctypes
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import oracle as zo
+from paper_2601_21198_amd import synth, zipmoe as zm
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 64          # int16 guard words on each side of every output buffer
+GUARD_WORD = 0x5A5A
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def gpu_decode_tensors(blobs, repeat_ids=None):
+    """Decodes each blob as a one-tensor expert; returns the decoded uint16 arrays (with guard check)."""
+    import torch
+    layer = zm.ExpertLayer([[b] for b in blobs])
+    ids = list(range(len(blobs))) if repeat_ids is None else repeat_ids
+    outs = []
+    ptrs = (ctypes.c_void_p * len(ids))()
+    for j, e in enumerate(ids):
+        n = int(layer.infos[e].n_values)
+        buf = torch.full((n + 2 * GUARD,), GUARD_WORD, dtype=torch.int16, device="cuda")
+        outs.append(buf)
+        ptrs[j] = buf.data_ptr() + 2 * GUARD
+    idarr = (ctypes.c_int32 * len(ids))(*ids)
+    zm.decode_experts(layer._ptr_blobs, layer._ptr_tables, layer._ptr_infos, layer.n_experts, 1,
+                      idarr, len(ids), ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p)),
+                      torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    res = []
+    for buf in outs:
+        a = buf.cpu().numpy().view(np.uint16)
+        assert np.all(a[:GUARD] == GUARD_WORD) and np.all(a[-GUARD:] == GUARD_WORD), "guard words overwritten"
+        res.append(a[GUARD:-GUARD].copy())
+    return res
+
+
+KINDS = ["all_equal", "two_exponents", "uniform_u16", "rare_last", "gauss", "wide"]
+SIZES = [0, 1, 7, 8, 9, 511, 512, 513, 4095, 4096, 4097, 9000, 3 * 16384 + 1234]
+
+
+@pytest.mark.parametrize("C,W,max_len", [(4096, 4096, 8), (16384, 4096, 8), (4096, 1024, 12), (2048, 512, 8),
+                                         (16384, 16384, 8), (8192, 2048, 12), (32768, 8192, 12)])
+def test_edge_cases_bit_exact(C, W, max_len):
+    tensors, blobs = [], []
+    for kind in KINDS:
+        for n in SIZES:
+            w = synth.special_tensor(kind, n, seed=n + 3)
+            blob, _ = zm.compress(w, C, W, max_len)
+            tensors.append(w)
+            blobs.append(blob)
+    say(f"edge cases C={C} W={W} L<={max_len}: {len(blobs)} tensors in one call")
+    got = gpu_decode_tensors(blobs)
+    for w, blob, g in zip(tensors, blobs, got):
+        assert np.array_equal(g, zo.decode(blob))        # against the reference decoder
+        assert np.array_equal(g, w)                      # and against the original: lossless
+
+
+def test_all_bit_patterns_and_duplicates():
+    w = np.random.default_rng(1).permutation(np.arange(65536, dtype=np.uint32)).astype(np.uint16)
+    blob8, _ = zm.compress(w, 4096, 4096, 8)
+    blob12, _ = zm.compress(w, 4096, 2048, 12)
+    got = gpu_decode_tensors([blob8, blob12], repeat_ids=[1, 0, 1, 1])      # duplicate ids are decoded again
+    for g in got:
+        assert np.array_equal(g, w)
+    assert np.array_equal(got[0], zo.decode(blob12))
+
+
+def test_bad_arguments_are_refused_on_the_host():
+    import torch
+    w = synth.special_tensor("gauss", 5000, 0)
+    blob, _ = zm.compress(w, 4096, 4096)
+    layer = zm.ExpertLayer([[blob]])
+    out = torch.empty(5008, dtype=torch.int16, device="cuda")
+    ptrs = (ctypes.c_void_p * 1)(out.data_ptr())
+    P = ctypes.POINTER(ctypes.c_void_p)
+    call = lambda ids, outs=ptrs, n=1: zm.decode_experts(layer._ptr_blobs, layer._ptr_tables, layer._ptr_infos, 1, 1,
+                                                         (ctypes.c_int32 * 1)(ids), n, ctypes.cast(outs, P), 0)
+    call(0)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint16)[:5000], w)
+    for bad_id in (-1, 1):
+        with pytest.raises(zm.ZipMoEError):
+            call(bad_id)
+    with pytest.raises(zm.ZipMoEError):
+        call(0, (ctypes.c_void_p * 1)(out.data_ptr() + 2))        # misaligned output
+    with pytest.raises(zm.ZipMoEError):
+        call(0, (ctypes.c_void_p * 1)(None))
+    call(0, n=0)                                                   # nothing selected: no launch, no error
+
+
+def oracle_decode_parallel(blobs, workers=16):
+    with ThreadPoolExecutor(workers) as ex:
+        return list(ex.map(zo.decode, blobs))
+
+
+def compress_expert(wl, layer, expert, stream_values=4096):
+    return [zm.compress(m, wl.chunk_values, stream_values)[0] for m in synth.expert_tensors(wl, layer, expert)]
+
+
+def test_config1_single_matrix():
+    w = synth.expert_matrix(synth.CFG1, 0, 0, 0)
+    lengths = zo.code_lengths(zo.histogram(zo.split(w)[0]), 8)
+    ref_blob = zo.encode(w, 4096, 4096, lengths)             # the reference encoder's own blob
+    got = gpu_decode_tensors([ref_blob])[0]
+    assert np.array_equal(got, zo.decode(ref_blob)) and np.array_equal(got, w.reshape(-1))
+
+
+def test_config2_one_expert_with_outliers():
+    import torch
+    wl = synth.CFG2
+    tensors = synth.expert_tensors(wl, 0, 0)
+    blobs = compress_expert(wl, 0, 0)
+    layer = zm.ExpertLayer([blobs])
+    bufs, starts, vals = layer.alloc_outputs(1)
+    layer.decode([0], bufs, starts, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = bufs[0].cpu().numpy().view(np.uint16)
+    ref = oracle_decode_parallel(blobs)
+    for m in range(3):
+        g = got[starts[m]: starts[m] + vals[m]]
+        assert np.array_equal(g, ref[m]) and np.array_equal(g, tensors[m].reshape(-1))
+
+
+def test_config3_layer_top8_zipf():
+    import torch
+    wl = synth.CFG3
+    say("config 3: generating and compressing 64 experts")
+    with ThreadPoolExecutor(16) as ex:
+        all_blobs = list(ex.map(lambda e: compress_expert(wl, 0, e), range(wl.n_experts)))
+    layer = zm.ExpertLayer(all_blobs, validate=False)
+    bufs, starts, vals = layer.alloc_outputs(wl.top_k)
+    stream = torch.cuda.current_stream().cuda_stream
+    for call in range(6):
+        ids = synth.route(wl, 0, call)
+        assert len(set(ids.tolist())) == wl.top_k
+        for b in bufs:
+            b.fill_(0x1111)
+        layer.decode(ids, bufs, starts, stream)
+        torch.cuda.synchronize()
+        say(f"config 3 call {call}: experts {ids.tolist()}")
+        flat = [all_blobs[e][m] for e in ids for m in range(3)]
+        ref = oracle_decode_parallel(flat) if call < 2 else None
+        for j, e in enumerate(ids):
+            got = bufs[j].cpu().numpy().view(np.uint16)
+            orig = synth.expert_tensors(wl, 0, int(e))
+            for m in range(3):
+                g = got[starts[m]: starts[m] + vals[m]]
+                assert np.array_equal(g, orig[m].reshape(-1))
+                if ref is not None:
+                    assert np.array_equal(g, ref[3 * j + m])

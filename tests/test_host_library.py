@@ -1,0 +1,120 @@
+"""The library's host side against the reference codec: same codebook cost, byte-identical blobs,
+blobs the reference decoder accepts, loadable C ABI."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle as zo
+from paper_2601_21198_amd import synth, zipmoe as zm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "zipmoe.h")).read()
+    declared = set(re.findall(r"\b(zm_[a-z_]+)\s*\(", text))
+    assert declared == set(zm.EXPORTS)
+    L = ctypes.CDLL(zm.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert zm.version() >= 100
+    assert zm.strerror(zm.E_FORMAT) and zm.strerror(12345)
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(zm.TensorInfo) == 72
+
+
+@pytest.mark.parametrize("kind,max_len", [("gauss", 8), ("gauss", 12), ("wide", 8), ("wide", 12), ("rare_last", 8),
+                                          ("two_exponents", 8), ("all_equal", 8), ("uniform_u16", 8)])
+def test_codebook_cost_equals_reference(kind, max_len):
+    w = synth.special_tensor(kind, 50000, seed=1)
+    hist = zm.exponent_histogram(w)
+    e, _ = zo.split(w)
+    assert np.array_equal(hist, zo.histogram(e))
+    mine, ref = zm.build_codebook(hist, max_len), zo.code_lengths(hist, max_len)
+    assert mine.max() <= max_len and np.array_equal(mine > 0, hist > 0)
+    assert int((hist * mine).sum()) == int((hist * ref).sum())
+    assert zo.kraft_units(mine) == zo.kraft_units(ref)
+
+
+def test_codebook_random_histograms():
+    rng = np.random.default_rng(0)
+    for trial in range(60):
+        k = int(rng.integers(1, 80))
+        hist = np.zeros(256, np.uint64)
+        hist[rng.choice(256, k, replace=False)] = rng.integers(1, 10 ** int(rng.integers(1, 7)), k)
+        for max_len in (8, 10, 12):
+            if k > 2 ** max_len:
+                continue
+            mine, ref = zm.build_codebook(hist, max_len), zo.code_lengths(hist, max_len)
+            assert int((hist * mine).sum()) == int((hist * ref).sum()), (trial, max_len)
+    with pytest.raises(zm.ZipMoEError):
+        zm.build_codebook(np.ones(256, np.uint64), 7)
+    with pytest.raises(zm.ZipMoEError):
+        zm.build_codebook(np.ones(256, np.uint64), 13)
+
+
+@pytest.mark.parametrize("kind", ["all_equal", "two_exponents", "uniform_u16", "rare_last", "gauss", "wide"])
+@pytest.mark.parametrize("n", [0, 1, 9, 511, 512, 513, 4096, 4097, 20000])
+def test_blobs_identical_to_reference_and_decodable(kind, n):
+    w = synth.special_tensor(kind, n, seed=n + 1)
+    for C, W, max_len in ((4096, 4096, 8), (4096, 1024, 12), (2048, 512, 8)):
+        lengths = zm.build_codebook(zm.exponent_histogram(w), max_len)
+        blob, offs = zm.encode(w, C, W, lengths)
+        ref = zo.encode(w, C, W, lengths)
+        assert blob.size == ref.size and np.array_equal(blob, ref)
+        assert np.array_equal(zo.decode(blob), w)
+        zm.validate_blob(blob)
+        info = zm.blob_info(blob)
+        h = zo.header(blob)
+        assert (info.n_values, info.chunk_values, info.stream_values, info.n_chunks, info.max_len,
+                info.round_symbols, info.n_present) == (n, C, W, h["n_chunks"], h["L"], h["R"], h["n_present"])
+        assert (info.lut_offset, info.table_offset, info.sm_offset, info.e_offset, info.blob_size) == \
+               (h["lut_offset"], h["table_offset"], h["sm_offset"], h["e_offset"], h["blob_size"])
+        table = blob[h["table_offset"]: h["table_offset"] + 8 * (h["n_chunks"] + 1)].view("<u8")
+        assert np.array_equal(offs, table)
+
+
+def test_workload_tensors_match_reference():
+    for wl, m in ((synth.CFG1, 0), (synth.CFG2, 2)):
+        w = synth.expert_matrix(wl, 0, 0, m)
+        blob, _ = zm.compress(w, wl.chunk_values, 4096, 8)
+        lengths = blob[128:384]
+        assert np.array_equal(blob, zo.encode(w, wl.chunk_values, 4096, lengths))
+        assert np.array_equal(zo.decode(blob), w.reshape(-1))
+
+
+def test_encode_rejects_bad_arguments():
+    w = synth.special_tensor("gauss", 5000, 0)
+    lengths = zm.build_codebook(zm.exponent_histogram(w), 8)
+    for C, W in ((4096, 1000), (4096 + 512, 1024), (0, 512), (512, 0)):
+        with pytest.raises(zm.ZipMoEError):
+            zm.encode(w, C, W, lengths)
+    short = lengths.copy()
+    short[int(np.argmax(lengths))] = 0            # a symbol that occurs has no code (and Kraft is no longer 1)
+    with pytest.raises(zm.ZipMoEError):
+        zm.encode(w, 4096, 1024, short)
+    over = lengths.copy()
+    over[lengths > 0] = 1                          # violates Kraft
+    with pytest.raises(zm.ZipMoEError):
+        zm.encode(w, 4096, 1024, over)
+
+
+def test_validate_rejects_damage():
+    w = synth.special_tensor("gauss", 3 * 4096, 2)
+    blob, offs = zm.compress(w, 4096, 2048)
+    zm.validate_blob(blob)
+    info = zm.blob_info(blob)
+    for off in (0, 4, 8, 16, 20, 24, 28, 32, 36, 40, 44, 56, 64, 72, 80, 88, 100,
+                128 + int(np.argmax(blob[128:384])), info.lut_offset + 3, info.table_offset, info.table_offset + 9,
+                int(offs[0]) & ~15, (int(offs[0]) & ~15) + 4, (int(offs[0]) & ~15) + 17, (int(offs[1]) & ~15) + 8):
+        bad = blob.copy()
+        bad[off] ^= 0x11
+        with pytest.raises(zm.ZipMoEError):
+            zm.validate_blob(bad)
+    with pytest.raises(zm.ZipMoEError):
+        zm.validate_blob(blob[:-256])
