@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched expert decode on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: every
+``zm_decode_experts`` call of one decode step of the workload (one call per MoE layer, each
+decoding that layer's routed top-k experts from their compressed form, resident in HBM, into bf16).
+
+Prints ONE JSON line: decompressed bf16 GB/s, the HBM-roofline fraction of the decode kernel
+(compressed bytes read + bf16 bytes written, per second, against 8 TB/s) and the reference codec's
+decoder timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X published peak HBM3E bandwidth
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def build_layer(wl, layer: int, stream_values: int, max_len: int, workers: int, keep_blobs_of=None):
+    """Generates and compresses every expert of one layer; returns (blobs per expert, algorithmic bytes per expert)."""
+    from paper_2601_21198_amd import synth, zipmoe as zm
+
+    def one(expert: int):
+        blobs, read_bytes, n_values = [], 0, 0
+        for m in synth.expert_tensors(wl, layer, expert):
+            blob, offs = zm.compress(m, wl.chunk_values, stream_values, max_len)
+            info = zm.blob_info(blob[:384])
+            # what one decode of this tensor must read: SM bytes, E-chunks, chunk table, decode table
+            read_bytes += int(info.n_values) + (int(offs[-1]) - int(info.e_offset)) + 8 * (int(info.n_chunks) + 1) + (2 << int(info.max_len))
+            n_values += int(info.n_values)
+            blobs.append(blob)
+        return blobs, read_bytes, n_values
+
+    with ThreadPoolExecutor(workers) as ex:
+        res = list(ex.map(one, range(wl.n_experts)))
+    return [r[0] for r in res], [r[1] for r in res], [r[2] for r in res]
+
+
+def cpu_baseline(sample_blobs, workers: int, budget_values: int):
+    """The reference decoder, as it stands, on ``workers`` host threads over chunk ranges of the sample."""
+    from oracle import oracle as zo
+
+    jobs, total = [], 0
+    for blob in sample_blobs:
+        h = zo.header(blob)
+        out = np.empty(h["n_values"], np.uint16)
+        step = max(1, -(-h["n_chunks"] // workers))
+        for c0 in range(0, h["n_chunks"], step):
+            c1 = min(h["n_chunks"], c0 + step)
+            jobs.append((blob, c0, c1, out))
+        total += h["n_values"]
+        if total >= budget_values:
+            break
+    zo.lib()
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(lambda j: zo.decode_chunks(*j), jobs))
+    dt = time.perf_counter() - t0
+    return 2.0 * total / dt / 1e9, total, dt
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--stream-values", type=int, default=4096)
+    ap.add_argument("--max-len", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verify", action="store_true", help="compare the last step's output with the originals")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="before the timed region, run a plain device copy of this many MiB three times "
+                         "(a kernel of known traffic that scales the profiler's HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; experts are independent, so more GPUs would each decode "
+              "their own experts with no exchange. Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2601_21198_amd import synth, zipmoe as zm
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 1
+    zm.lib()
+    wl = synth.WORKLOADS[args.workload]
+    workers = min(16, os.cpu_count() or 1)
+    default_steps = {"cfg2": (2000, 200), "cfg3": (1000, 100), "cfg4": (200, 20), "cfg5": (40, 4)}[args.workload]
+    steps = args.steps if args.steps is not None else default_steps[0]
+    warmup = args.warmup if args.warmup is not None else default_steps[1]
+
+    # ---- build the compressed model, layer by layer, and make it resident in HBM
+    t0 = time.perf_counter()
+    layers, read_bytes, n_values, sample_blobs = [], [], [], []
+    compressed_total = 0
+    for layer in range(wl.n_layers):
+        blobs, rb, nv = build_layer(wl, layer, args.stream_values, args.max_len, workers)
+        L = zm.ExpertLayer(blobs, validate=(layer == 0))
+        compressed_total += L.compressed_bytes
+        layers.append(L)
+        read_bytes.append(rb)
+        n_values.append(nv)
+        if layer == 0:
+            first_ids = synth.route(wl, 0, 0)
+            sample_blobs = [b for e in first_ids for b in blobs[int(e)]]
+        if wl.n_layers > 1:
+            log(f"layer {layer + 1}/{wl.n_layers} resident ({time.perf_counter() - t0:.0f} s)")
+    raw_total = 2 * sum(sum(nv) for nv in n_values)
+    log(f"{wl.name}: {raw_total / 1e9:.2f} GB bf16 -> {compressed_total / 1e9:.2f} GB resident "
+        f"({compressed_total / raw_total:.4f}) in {time.perf_counter() - t0:.1f} s")
+
+    # ---- pre-marshalled calls: one per (step, layer); routing differs from call to call
+    stream = torch.cuda.current_stream().cuda_stream
+    out_sets = [layers[0].alloc_outputs(wl.top_k) for _ in range(2)]        # two output sets, alternated
+    n_distinct = min(steps + warmup, 64)
+    calls, call_bytes, call_out_bytes = [], [], []
+    for s in range(n_distinct):
+        per_step = []
+        for layer in range(wl.n_layers):
+            ids = synth.route(wl, layer, s)
+            bufs, starts, _ = out_sets[(s * wl.n_layers + layer) % 2]
+            per_step.append(layers[layer].make_call(ids, bufs, starts))
+            ob = sum(2 * n_values[layer][int(e)] for e in ids)
+            call_out_bytes.append(ob)
+            call_bytes.append(ob + sum(read_bytes[layer][int(e)] for e in ids))
+        calls.append(per_step)
+
+    def run(k0: int, k: int) -> None:
+        for s in range(k0, k0 + k):
+            for c in calls[s % n_distinct]:
+                c(stream)
+
+    if args.copy_mib:
+        src = torch.full((args.copy_mib << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    run(0, warmup)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_start = time.perf_counter()
+    ev0.record()
+    run(warmup, steps)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    gpu_ms = ev0.elapsed_time(ev1)
+
+    launches = steps * wl.n_layers
+    idx = [((warmup + s) % n_distinct) * wl.n_layers + l for s in range(steps) for l in range(wl.n_layers)]
+    out_bytes = float(sum(call_out_bytes[i] for i in idx))
+    alg_bytes = float(sum(call_bytes[i] for i in idx))
+    value = out_bytes / wall / 1e9
+    kernel_s = gpu_ms / 1e3 / launches
+    achieved = alg_bytes / launches / kernel_s / 1e9
+
+    if args.verify:
+        s_last = (warmup + steps - 1) % n_distinct
+        for layer in range(wl.n_layers - 1, max(-1, wl.n_layers - 3), -1):
+            ids = synth.route(wl, layer, s_last)
+            bufs, starts, vals = out_sets[(s_last * wl.n_layers + layer) % 2]
+            for j, e in enumerate(ids):
+                got = bufs[j].cpu().numpy().view(np.uint16)
+                for m, t in enumerate(synth.expert_tensors(wl, layer, int(e))):
+                    assert np.array_equal(got[starts[m]: starts[m] + vals[m]], t.reshape(-1)), (layer, e, m)
+        log("verify: outputs of the last step equal the original tensors")
+
+    result = {
+        "metric": "decompressed bf16 GB/s per GPU; % of HBM roofline (bytes read+written)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": round(wall * 1e3 / steps, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name,
+            "calls_per_step": wl.n_layers,
+            "top_k": wl.top_k,
+            "chunk_values": wl.chunk_values,
+            "stream_values": args.stream_values,
+            "max_code_len": args.max_len,
+            "bf16_bytes_per_step": out_bytes / steps,
+            "compressed_resident_bytes": compressed_total,
+            "compression_ratio": round(compressed_total / raw_total, 4),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+            "kernel": "zm_decode_kernel<4,4>",
+            "kernel_us": round(kernel_s * 1e6, 2),
+            "algorithmic_bytes_per_launch": alg_bytes / launches,
+            "algorithmic_bytes_per_value": round(alg_bytes / (out_bytes / 2), 4),
+        },
+    }
+    if not args.no_cpu_baseline:
+        # about 10-30 s of host work: the reference decoder runs about 2 M values/s per thread
+        budget = 2_500_000 * workers * 8
+        gbps, n, dt = cpu_baseline(sample_blobs, workers, budget)
+        result["cpu_baseline"] = {
+            "value": round(gbps, 4), "unit": "GB/s", "cores": workers, "kind": "oracle",
+            "sample": f"tensors of the first call's routed experts, {n} values, decoded in {dt:.1f} s",
+        }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
