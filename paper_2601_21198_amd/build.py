@@ -7,7 +7,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
-LIB_PATH = os.path.join(_HERE, "libzipmoe.so")
+# ZIPMOE_LIBRARY points the binding at another build of the same sources (same ABI)
+LIB_PATH = os.environ.get("ZIPMOE_LIBRARY", os.path.join(_HERE, "libzipmoe.so"))
 SOURCES = [os.path.join(CSRC, "zipmoe_host.cpp"), os.path.join(CSRC, "zipmoe_decode.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -47,16 +47,17 @@ struct Task {
     uint32_t stream_values;
     uint32_t streams_per_chunk;
     uint32_t n_streams;
-    uint32_t first_block;
     uint32_t max_len;
+    uint32_t pad;
 };
 
 struct Launch {
     uint32_t n_tasks;
     uint32_t stream_cap_words;   // LDS words reserved per wave for its stream
     uint32_t pad[2];
-    Task task[kMaxTasks];
+    Task task[kMaxTasks];              // blockIdx.y selects the task
 };
+static_assert(sizeof(Launch) <= 4096, "kernel arguments must stay under 4 KiB");
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 {
@@ -72,6 +73,75 @@ __device__ __forceinline__ void recover4(uint32_t e4, uint32_t sm4, uint32_t &w0
     const uint32_t lo4 = ((e4 << 7) & 0x80808080u) | (sm4 & 0x7F7F7F7Fu);   // e mmmmmmm
     w01 = __builtin_amdgcn_perm(hi4, lo4, 0x05010400u);
     w23 = __builtin_amdgcn_perm(hi4, lo4, 0x07030602u);
+}
+
+constexpr int kGroup = 8;          // tiles per group: their sign-mantissa loads are issued together
+
+// Lock-step decoder state of one lane (a5, a6).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes of recovered bf16 words; the output is written once and not read again by this kernel
+__device__ __forceinline__ void store_words(uint16_t *dst, const uint4 &w)
+{
+#ifdef ZM_NT_STORE
+    __builtin_nontemporal_store((u32x4){w.x, w.y, w.z, w.w}, reinterpret_cast<u32x4 *>(dst));
+#else
+    *reinterpret_cast<uint4 *>(dst) = w;
+#endif
+}
+
+template <int R>
+struct Decoder {
+    const uint16_t *lut;
+    const uint32_t *words;
+    uint32_t last_word;
+    uint32_t lo = 0, hi = 0;      // words q and q+1 of this lane's bitstream
+    uint32_t pos = 0;             // bits of lo already used (< 32 at the start of a round)
+    uint32_t next = 128;          // next unread word of the stream (uniform over the wave)
+
+    // Decodes this lane's eight exponent bytes of one tile.
+    __device__ __forceinline__ uint2 tile()
+    {
+        constexpr uint32_t kMask = (R == 4 ? 256u : 4096u) - 1u;
+        uint32_t e[2] = {0u, 0u};
+#pragma unroll
+        for (int r = 0; r < 8 / R; ++r) {
+            // R symbols out of one 32-bit window
+            uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                const uint32_t ent = lut[win & kMask];
+                const uint32_t len = ent >> 8;
+                e[(r * R + k) >> 2] |= (ent & 0xFFu) << (8 * ((r * R + k) & 3));
+                win >>= len;
+                pos += len;
+            }
+            // lanes that crossed a word boundary take the stream's next words, in lane order: the
+            // ballot's prefix count is each taker's offset.  (After the stream's last round the word
+            // read here is never used.)
+            const bool take = pos >= 32u;
+            const uint64_t takers = __ballot(take);
+            if (takers) {
+                const uint32_t idx = min(next + lanes_below(takers), last_word);
+                if (take) { lo = hi; hi = words[idx]; pos -= 32u; }
+                next += static_cast<uint32_t>(__builtin_popcountll(takers));
+            }
+        }
+        return make_uint2(e[0], e[1]);
+    }
+};
+
+// Requests the sign-mantissa bytes of tiles first .. first+kGroup-1 (zero where the lane has none).
+__device__ __forceinline__ void load_sm_group(uint2 (&sm)[kGroup], const uint8_t *sm_base, int32_t mine,
+                                              uint32_t first, uint32_t tiles)
+{
+#pragma unroll
+    for (int k = 0; k < kGroup; ++k) {
+        const uint32_t tile = first + k;
+        sm[k] = make_uint2(0u, 0u);
+        if (tile < tiles && mine - static_cast<int32_t>(tile * kTile) > 0)
+            sm[k] = *reinterpret_cast<const uint2 *>(sm_base + tile * kTile);
+    }
 }
 
 // R: symbols per round; kWaves: waves (streams) per workgroup
@@ -92,35 +162,54 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    uint32_t ti = 0;
-    while (ti + 1 < P.n_tasks && blockIdx.x >= P.task[ti + 1].first_block) ++ti;
-    const Task &t = P.task[ti];
+    // grid: x = workgroup inside the tensor, y = tensor.  The task is copied with one batch of scalar loads.
+    const Task t = P.task[blockIdx.y];
 
     uint16_t *lut = reinterpret_cast<uint16_t *>(smem) + (G::kLutPerWave ? wave * G::kLutEntries : 0);
     uint32_t *words = smem + G::kLutWords + wave * P.stream_cap_words;
 
-    // a3: decode table -> LDS, replicated over the index bits above the longest code
-    {
-        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.blob + t.lut_offset);
-        const uint32_t mask = (1u << t.max_len) - 1u;
-        if (G::kLutPerWave) {
-            for (uint32_t i = lane; i < G::kLutEntries; i += 64) lut[i] = src[i & mask];
-        } else {
-            for (uint32_t i = threadIdx.x; i < G::kLutEntries; i += 64 * kWaves) lut[i] = src[i & mask];
-        }
-    }
-
-    const uint32_t g = (blockIdx.x - t.first_block) * kWaves + wave;
+    const uint32_t g = blockIdx.x * kWaves + wave;
     bool active = g < t.n_streams;
     const uint32_t W = t.stream_values;
     const uint64_t v0 = static_cast<uint64_t>(g) * W;              // first value of the stream in the tensor
     uint32_t sn = 0, mode = ZM_MODE_RAW, tiles = 0;
     const uint8_t *raw = nullptr;
     if (active) {
-        const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
         const uint64_t rest = t.n_values - v0;
         sn = rest < W ? static_cast<uint32_t>(rest) : W;
         tiles = (sn + kTile - 1) / kTile;
+    }
+    const uint8_t *sm_base = t.blob + t.sm_offset + v0 + lane * 8u;
+    const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
+
+    // The sign-mantissa bytes of the first kGroup tiles are requested before anything else: their
+    // addresses need no lookup, and they stay in flight while the stream is staged.
+    uint2 sm[kGroup];
+    load_sm_group(sm, sm_base, mine, 0, tiles);
+
+    // a3: decode table -> LDS, replicated over the index bits above the longest code.  All of a lane's
+    // loads are issued before the first is used.
+    {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.blob + t.lut_offset);
+        const uint32_t mask = (1u << t.max_len) - 1u;
+        if (G::kLutPerWave) {
+            // 256 entries, four per lane
+            const uint32_t i = 4u * lane;
+            const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
+            reinterpret_cast<uint2 *>(lut)[lane] = make_uint2(a | (b << 16), c | (d << 16));
+        } else {
+            // 4096 entries; R = 2 implies max_len >= 9, so any 16 consecutive entries stay consecutive under the mask
+            for (uint32_t i = 16u * threadIdx.x; i < G::kLutEntries; i += 16u * 64u * kWaves) {
+                const uint4 *v = reinterpret_cast<const uint4 *>(src + (i & mask));
+                const uint4 x = v[0], y = v[1];
+                reinterpret_cast<uint4 *>(lut + i)[0] = x;
+                reinterpret_cast<uint4 *>(lut + i)[1] = y;
+            }
+        }
+    }
+
+    if (active) {
+        const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
         const uint64_t ent = t.table[c];
         const uint64_t at = ent & ~15ull;
         mode = static_cast<uint32_t>(ent & 15ull);
@@ -149,84 +238,66 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         }
     }
     if (G::kLutPerWave) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        // LDS written by some lanes of this wave is read by others: order the LDS accesses only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
     } else {
         __syncthreads();
     }
     if (!active) return;
 
-    const uint8_t *sm_base = t.blob + t.sm_offset + v0 + lane * 8u;
     uint16_t *out_base = t.out + v0 + lane * 8u;
-    const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
 
     // decoder state
-    uint32_t lo = 0, hi = 0, pos = 0, next = 128;
+    Decoder<R> dec;
+    dec.lut = lut; dec.words = words; dec.last_word = P.stream_cap_words - 1u;
     if (mode == ZM_MODE_CODED) {
         const uint2 first = reinterpret_cast<const uint2 *>(words)[lane];
-        lo = first.x; hi = first.y;
+        dec.lo = first.x; dec.hi = first.y;
     }
-    const uint32_t last_word = P.stream_cap_words - 1u;
 
-    uint2 sm = make_uint2(0u, 0u);
-    if (mine > 0) sm = *reinterpret_cast<const uint2 *>(sm_base);
-
-    for (uint32_t tile = 0; tile < tiles; ++tile) {
-        const int32_t left = mine - static_cast<int32_t>(tile * kTile);
-        // sign-mantissa bytes of the next tile, requested before this tile's decode
-        uint2 sm_next = make_uint2(0u, 0u);
-        if (tile + 1 < tiles && left - static_cast<int32_t>(kTile) > 0)
-            sm_next = *reinterpret_cast<const uint2 *>(sm_base + (tile + 1) * kTile);
-
-        uint32_t e[2];
-        if (mode == ZM_MODE_CODED) {
+    // Common case, straight-line: a full coded stream of exactly kGroup tiles.  All loads were issued
+    // above; from here on the wave only computes and stores.
+    if (mode == ZM_MODE_CODED && sn == kGroup * kTile) {
 #pragma unroll
-            for (int r = 0; r < 8 / R; ++r) {
-                // a5: R symbols from one 32-bit window
-                uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
-                uint32_t acc = 0;
+        for (int k = 0; k < kGroup; ++k) {
+            const uint2 ev = dec.tile();
+            uint4 w;
+            recover4(ev.x, sm[k].x, w.x, w.y);
+            recover4(ev.y, sm[k].y, w.z, w.w);
+            store_words(out_base + k * kTile, w);
+        }
+        return;
+    }
+    for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
+        uint2 sm_next[kGroup];
+        load_sm_group(sm_next, sm_base, mine, g0 + kGroup, tiles);
 #pragma unroll
-                for (int k = 0; k < R; ++k) {
-                    const uint32_t ent = lut[win & (G::kLutEntries - 1u)];
-                    const uint32_t len = ent >> 8;
-                    acc |= (ent & 0xFFu) << (8 * ((r * R + k) & 3));
-                    win >>= len;
-                    pos += len;
-                }
-                if (R == 4) e[r] = acc;
-                else if ((r & 1) == 0) e[r >> 1] = acc;
-                else e[r >> 1] |= acc;
-                // a6: lanes that crossed a word boundary take the stream's next words, in lane order
-                if (!(tile + 1 == tiles && r == 8 / R - 1)) {
-                    const bool take = pos >= 32u;
-                    const uint64_t takers = __ballot(take);
-                    if (takers) {
-                        const uint32_t idx = min(next + lanes_below(takers), last_word);
-                        if (take) { lo = hi; hi = words[idx]; pos -= 32u; }
-                        next += static_cast<uint32_t>(__builtin_popcountll(takers));
-                    }
+        for (int k = 0; k < kGroup; ++k) {
+            const uint32_t tile = g0 + k;
+            if (tile < tiles) {
+                const int32_t left = mine - static_cast<int32_t>(tile * kTile);
+                uint2 ev = make_uint2(0u, 0u);
+                if (mode == ZM_MODE_CODED) ev = dec.tile();
+                else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
+                // a8: recovery and store
+                uint4 w;
+                recover4(ev.x, sm[k].x, w.x, w.y);
+                recover4(ev.y, sm[k].y, w.z, w.w);
+                uint16_t *dst = out_base + tile * kTile;
+                if (left >= 8) {
+                    store_words(dst, w);
+                } else if (left > 0) {
+                    const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        if (q < left) dst[q] = static_cast<uint16_t>(ws[q >> 1] >> (16 * (q & 1)));
                 }
             }
-        } else {
-            uint2 ev = make_uint2(0u, 0u);
-            if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
-            e[0] = ev.x; e[1] = ev.y;
         }
-
-        // a8: recovery and store
-        uint4 w;
-        recover4(e[0], sm.x, w.x, w.y);
-        recover4(e[1], sm.y, w.z, w.w);
-        uint16_t *dst = out_base + tile * kTile;
-        if (left >= 8) {
-            *reinterpret_cast<uint4 *>(dst) = w;
-        } else if (left > 0) {
-            const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (k < left) dst[k] = static_cast<uint16_t>(ws[k >> 1] >> (16 * (k & 1)));
-        }
-        sm = sm_next;
+        for (int k = 0; k < kGroup; ++k) sm[k] = sm_next[k];
     }
 }
 
@@ -248,13 +319,13 @@ int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
         if constexpr (kWaves > 1) return launch_tasks<R, kWaves / 2>(L, cap, stream);
         else return ZM_E_ARG;                   // stream too long to stage in LDS
     }
-    uint32_t blocks = 0;
+    uint32_t blocks = 0;            // of the largest tensor; workgroups past a smaller tensor's end exit at once
     for (uint32_t k = 0; k < L.n_tasks; ++k) {
-        L.task[k].first_block = blocks;
-        blocks += (L.task[k].n_streams + kWaves - 1) / kWaves;
+        const uint32_t b = (L.task[k].n_streams + kWaves - 1) / kWaves;
+        blocks = b > blocks ? b : blocks;
     }
     if (!blocks) return ZM_OK;
-    hipLaunchKernelGGL((zm_decode_kernel<R, kWaves>), dim3(blocks), dim3(64 * kWaves), lds, stream, L);
+    hipLaunchKernelGGL((zm_decode_kernel<R, kWaves>), dim3(blocks, L.n_tasks), dim3(64 * kWaves), lds, stream, L);
     return hipGetLastError() == hipSuccess ? ZM_OK : ZM_E_HIP;
 }
 
@@ -326,7 +397,7 @@ extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const
             t.stream_values = ti.stream_values;
             t.streams_per_chunk = ti.chunk_values / ti.stream_values;
             t.n_streams = static_cast<uint32_t>(n_streams);
-            t.first_block = 0;
+            t.pad = 0;
             t.max_len = ti.max_len;
             if (ti.round_symbols == 4) t4[n4++] = t; else t2[n2++] = t;
         }
