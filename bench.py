@@ -26,6 +26,26 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X published peak HBM3E bandwidth
 
+# HBM bytes per launch of the decode kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain
+# copy of known size; the summaries are under profiles/).  Valid only for the kernel source they were taken
+# with: the entry is reported only while the source's hash still matches, else "traffic" is null.
+MEASURED_TRAFFIC = {
+    "kernel_sha256_16": "f72c5627153bb645",
+    "bytes_per_launch": {"cfg5": 118.87e6, "cfg4": 1214.05e6},
+}
+
+
+def measured_traffic(workload: str):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2601_21198_amd", "csrc", "zipmoe_decode.hip")
+    try:
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if digest != MEASURED_TRAFFIC["kernel_sha256_16"]:
+        return None
+    return MEASURED_TRAFFIC["bytes_per_launch"].get(workload)
+
 
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -51,27 +71,31 @@ def build_layer(wl, layer: int, stream_values: int, max_len: int, workers: int, 
     return [r[0] for r in res], [r[1] for r in res], [r[2] for r in res]
 
 
-def cpu_baseline(sample_blobs, workers: int, budget_values: int):
-    """The reference decoder, as it stands, on ``workers`` host threads over chunk ranges of the sample."""
+def cpu_baseline(sample_blobs, workers: int, min_seconds: float = 10.0):
+    """The reference decoder, as it stands, on ``workers`` host threads: chunk ranges of the sample tensors,
+    whole passes over the sample repeated until ``min_seconds`` have gone by."""
     from oracle import oracle as zo
 
-    jobs, total = [], 0
+    jobs, per_pass = [], 0
     for blob in sample_blobs:
         h = zo.header(blob)
         out = np.empty(h["n_values"], np.uint16)
         step = max(1, -(-h["n_chunks"] // workers))
         for c0 in range(0, h["n_chunks"], step):
-            c1 = min(h["n_chunks"], c0 + step)
-            jobs.append((blob, c0, c1, out))
-        total += h["n_values"]
-        if total >= budget_values:
-            break
+            jobs.append((blob, c0, min(h["n_chunks"], c0 + step), out))
+        per_pass += h["n_values"]
     zo.lib()
+    total, passes = 0, 0
     t0 = time.perf_counter()
     with ThreadPoolExecutor(workers) as ex:
-        list(ex.map(lambda j: zo.decode_chunks(*j), jobs))
+        while True:
+            list(ex.map(lambda j: zo.decode_chunks(*j), jobs))
+            total += per_pass
+            passes += 1
+            if time.perf_counter() - t0 >= min_seconds or passes >= 64:
+                break
     dt = time.perf_counter() - t0
-    return 2.0 * total / dt / 1e9, total, dt
+    return 2.0 * total / dt / 1e9, total, dt, passes
 
 
 def main() -> int:
@@ -215,7 +239,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(args.workload),
             "kernel": "zm_decode_kernel<4,4>",
             "kernel_us": round(kernel_s * 1e6, 2),
             "algorithmic_bytes_per_launch": alg_bytes / launches,
@@ -223,12 +247,11 @@ def main() -> int:
         },
     }
     if not args.no_cpu_baseline:
-        # about 10-30 s of host work: the reference decoder runs about 2 M values/s per thread
-        budget = 2_500_000 * workers * 8
-        gbps, n, dt = cpu_baseline(sample_blobs, workers, budget)
+        gbps, n, dt, passes = cpu_baseline(sample_blobs, workers)
         result["cpu_baseline"] = {
             "value": round(gbps, 4), "unit": "GB/s", "cores": workers, "kind": "oracle",
-            "sample": f"tensors of the first call's routed experts, {n} values, decoded in {dt:.1f} s",
+            "sample": f"the {len(sample_blobs)} tensors of the first call's routed experts, {passes} passes, "
+                      f"{n} values decoded in {dt:.1f} s",
         }
     print(json.dumps(result), flush=True)
     return 0

@@ -1,0 +1,114 @@
+"""GPU parity at the full sizes of configurations 4 and 5, in the launch shape bench.py times.
+
+Every call's output is compared on the device with the original tensors (the codec is lossless, so the
+original is the unique correct result), and sampled chunk ranges are decoded by the reference codec on
+the host and compared element by element."""
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import oracle as zo
+from paper_2601_21198_amd import synth, zipmoe as zm
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def build_layer(wl, layer, workers=16):
+    """(blobs per expert, originals per expert as device int16 tensors, flat per expert)"""
+    import torch
+
+    def one(e):
+        tensors = synth.expert_tensors(wl, layer, e)
+        blobs = [zm.compress(t, wl.chunk_values, 4096)[0] for t in tensors]
+        flat = np.concatenate([t.reshape(-1) for t in tensors]).view(np.int16)
+        return blobs, flat
+
+    with ThreadPoolExecutor(workers) as ex:
+        res = list(ex.map(one, range(wl.n_experts)))
+    originals = [torch.from_numpy(r[1]).cuda() for r in res]
+    return [r[0] for r in res], originals
+
+
+def oracle_sample_check(rng, blobs_of_expert, got_flat, starts, n_ranges=6, span=4):
+    """decode a few chunk ranges of each tensor with the reference codec and compare"""
+    for m, blob in enumerate(blobs_of_expert):
+        h = zo.header(blob)
+        scratch = np.zeros(h["n_values"], np.uint16)
+        for _ in range(n_ranges):
+            c0 = int(rng.integers(0, max(1, h["n_chunks"] - span)))
+            c1 = min(h["n_chunks"], c0 + span)
+            zo.decode_chunks(blob, c0, c1, scratch)
+            lo, hi = c0 * h["chunk_values"], min(h["n_values"], c1 * h["chunk_values"])
+            assert np.array_equal(got_flat[starts[m] + lo: starts[m] + hi], scratch[lo:hi])
+        # the last chunk too (ragged tails live there)
+        zo.decode_chunks(blob, h["n_chunks"] - 1, h["n_chunks"], scratch)
+        lo = (h["n_chunks"] - 1) * h["chunk_values"]
+        assert np.array_equal(got_flat[starts[m] + lo: starts[m] + h["n_values"]], scratch[lo:])
+
+
+def test_config4_thousand_calls_top2():
+    import torch
+    wl = synth.CFG4
+    say("config 4: generating and compressing 8 experts of 3 x 58.7 M values")
+    blobs, originals = build_layer(wl, 0)
+    layer = zm.ExpertLayer(blobs, validate=False)
+    for b in blobs[0]:
+        zm.validate_blob(b)
+    bufs, starts, vals = layer.alloc_outputs(wl.top_k)
+    assert starts == [0, vals[0], vals[0] + vals[1]]
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(4)
+    for call in range(wl.n_calls):
+        ids = synth.route(wl, 0, call)
+        assert ids[0] != ids[1]
+        layer.decode(ids, bufs, starts, stream)
+        for j, e in enumerate(ids):
+            assert torch.equal(bufs[j], originals[int(e)]), (call, int(e))
+        if call in (0, 499, 999):
+            say(f"config 4 call {call}: experts {ids.tolist()} equal to the originals; sampling the reference decoder")
+            for j, e in enumerate(ids):
+                oracle_sample_check(rng, blobs[int(e)], bufs[j].cpu().numpy().view(np.uint16), starts)
+        if call % 5 == 0:
+            for b in bufs:
+                b.zero_()                                     # stale data can not pass for a decode
+
+
+def test_config5_full_model_256_steps_top4():
+    import torch
+    wl = synth.CFG5
+    layers, originals, keep_blobs = [], [], {}
+    sample_layers = (0, 11, 23)
+    for l in range(wl.n_layers):
+        blobs, orig = build_layer(wl, l)
+        layers.append(zm.ExpertLayer(blobs, validate=(l == 0)))
+        originals.append(orig)
+        if l in sample_layers:
+            keep_blobs[l] = blobs
+        if l % 6 == 5:
+            say(f"config 5: {l + 1}/{wl.n_layers} layers resident")
+    resident = sum(L.compressed_bytes for L in layers)
+    say(f"config 5: {resident / 1e9:.2f} GB compressed resident for {2 * 12457082880 / 1e9:.2f} GB of bf16")
+    bufs, starts, vals = layers[0].alloc_outputs(wl.top_k)
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(5)
+    ok = torch.ones((), dtype=torch.bool, device="cuda")
+    for step in range(wl.n_calls):
+        for l in range(wl.n_layers):
+            ids = synth.route(wl, l, step)
+            layers[l].decode(ids, bufs, starts, stream)
+            for j, e in enumerate(ids):
+                ok &= (bufs[j] == originals[l][int(e)]).all()
+            if l in sample_layers and step in (0, 255):
+                for j, e in enumerate(ids[:2]):
+                    oracle_sample_check(rng, keep_blobs[l][int(e)], bufs[j].cpu().numpy().view(np.uint16), starts, 3, 2)
+        if step % 32 == 31:
+            assert bool(ok), f"mismatch at or before step {step}"
+            say(f"config 5: {step + 1} steps x 24 layers bit-exact")
+    assert bool(ok)
