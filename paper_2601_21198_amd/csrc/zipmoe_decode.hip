@@ -7,23 +7,25 @@
 // step of Sec. 3.3) without the exponents ever leaving registers.
 //
 // Work decomposition
-//   grid    one workgroup per kWaves consecutive streams of one tensor
+//   grid    x: workgroups of kWaves consecutive streams, y: tensor
 //   wave    one stream: stream_values consecutive values, tiles of 512
 //   lane j  owns values 8j..8j+7 of every tile: one 64-bit load of
 //           sign-mantissa bytes and one 128-bit store of bf16 words per tile,
 //           both contiguous across the wave (512 B and 1 KiB per instruction)
 //
 // Per wave
-//   1. the decode table goes to LDS (a3), replicated to the full index width so
-//      the lookup index needs no per-tensor mask;
-//   2. the stream's words are copied from HBM to LDS with 128-bit loads (a4);
-//   3. lock-step decode (a5): every lane keeps two words (lo, hi) of its own
+//   1. the stream's words are requested with 128-bit loads (a4) -- first, because
+//      decoding can not start without them -- and go to LDS;
+//   2. the sign-mantissa bytes of the stream's first eight tiles are requested;
+//   3. the decode table goes to LDS (a3) as two byte tables (code length, symbol)
+//      at fixed LDS addresses, replicated to the full index width;
+//   4. lock-step decode (a5): every lane keeps two words (lo, hi) of its own
 //      bitstream and a bit position; per round it extracts a 32-bit window with
 //      one funnel shift and decodes R symbols by table lookup;
-//   4. after a round the lanes whose position passed 32 bits take the next
+//   5. after a round the lanes whose position passed 32 bits take the next
 //      words of the stream: a ballot marks them, a prefix count over the ballot
 //      (mbcnt) gives each its word (a6);
-//   5. the eight decoded exponent bytes are merged with the sign-mantissa bytes
+//   6. the eight decoded exponent bytes are merged with the sign-mantissa bytes
 //      by byte-parallel bit operations and stored (a8).
 #include <hip/hip_runtime.h>
 
@@ -35,6 +37,7 @@ namespace {
 
 constexpr int kMaxTasks = 48;     // tensors per launch; 72 B each keeps the kernel arguments under 4 KiB
 constexpr uint32_t kTile = 512;
+constexpr int kGroup = 8;         // tiles whose sign-mantissa loads are in flight together
 
 struct Task {
     const uint8_t *blob;
@@ -55,7 +58,7 @@ struct Launch {
     uint32_t n_tasks;
     uint32_t stream_cap_words;   // LDS words reserved per wave for its stream
     uint32_t pad[2];
-    Task task[kMaxTasks];              // blockIdx.y selects the task
+    Task task[kMaxTasks];        // blockIdx.y selects the task
 };
 static_assert(sizeof(Launch) <= 4096, "kernel arguments must stay under 4 KiB");
 
@@ -75,24 +78,34 @@ __device__ __forceinline__ void recover4(uint32_t e4, uint32_t sm4, uint32_t &w0
     w23 = __builtin_amdgcn_perm(hi4, lo4, 0x07030602u);
 }
 
-constexpr int kGroup = 8;          // tiles per group: their sign-mantissa loads are issued together
-
-// Lock-step decoder state of one lane (a5, a6).
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// 16 bytes of recovered bf16 words; the output is written once and not read again by this kernel
-__device__ __forceinline__ void store_words(uint16_t *dst, const uint4 &w)
+__device__ __forceinline__ void recover_and_store(uint16_t *dst, uint2 e, uint2 sm)
 {
-#ifdef ZM_NT_STORE
-    __builtin_nontemporal_store((u32x4){w.x, w.y, w.z, w.w}, reinterpret_cast<u32x4 *>(dst));
-#else
+    uint4 w;
+    recover4(e.x, sm.x, w.x, w.y);
+    recover4(e.y, sm.y, w.z, w.w);
     *reinterpret_cast<uint4 *>(dst) = w;
-#endif
+}
+
+// Same for a lane that owns fewer than eight values of the tile.
+__device__ __forceinline__ void recover_and_store_partial(uint16_t *dst, uint2 e, uint2 sm, int32_t left)
+{
+    uint32_t ws[4];
+    recover4(e.x, sm.x, ws[0], ws[1]);
+    recover4(e.y, sm.y, ws[2], ws[3]);
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+        if (q < left) dst[q] = static_cast<uint16_t>(ws[q >> 1] >> (16 * (q & 1)));
 }
 
 template <int R>
+struct Code {
+    static constexpr int kIndexBits = R == 4 ? 8 : 12;     // R = 4 iff the longest code has at most 8 bits
+    static constexpr uint32_t kEntries = 1u << kIndexBits;
+};
+
+// Lock-step decoder state of one lane (a5, a6).  len_tab / sym_tab are the workgroup's byte tables.
+template <int R>
 struct Decoder {
-    const uint16_t *lut;
     const uint32_t *words;
     uint32_t last_word;
     uint32_t lo = 0, hi = 0;      // words q and q+1 of this lane's bitstream
@@ -100,21 +113,27 @@ struct Decoder {
     uint32_t next = 128;          // next unread word of the stream (uniform over the wave)
 
     // Decodes this lane's eight exponent bytes of one tile.
-    __device__ __forceinline__ uint2 tile()
+    __device__ __forceinline__ uint2 tile(const uint8_t *len_tab, const uint8_t *sym_tab)
     {
-        constexpr uint32_t kMask = (R == 4 ? 256u : 4096u) - 1u;
+        constexpr uint32_t kMask = Code<R>::kEntries - 1u;
         uint32_t e[2] = {0u, 0u};
 #pragma unroll
         for (int r = 0; r < 8 / R; ++r) {
-            // R symbols out of one 32-bit window
-            uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
+            // R symbols out of one 32-bit window; `used` is the bit offset of the next code in it
+            const uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
+            uint32_t used = 0;
+            uint32_t s[R];
 #pragma unroll
             for (int k = 0; k < R; ++k) {
-                const uint32_t ent = lut[win & kMask];
-                const uint32_t len = ent >> 8;
-                e[(r * R + k) >> 2] |= (ent & 0xFFu) << (8 * ((r * R + k) & 3));
-                win >>= len;
-                pos += len;
+                const uint32_t idx = (win >> used) & kMask;
+                s[k] = sym_tab[idx];
+                used += len_tab[idx];
+            }
+            pos += used;
+            if (R == 4) {
+                e[r] = (s[0] | (s[1] << 8)) | ((s[2] | (s[3] << 8)) << 16);
+            } else {
+                e[r >> 1] |= (s[0] | (s[1] << 8)) << (16 * (r & 1));
             }
             // lanes that crossed a word boundary take the stream's next words, in lane order: the
             // ballot's prefix count is each taker's offset.  (After the stream's last round the word
@@ -131,42 +150,23 @@ struct Decoder {
     }
 };
 
-// Requests the sign-mantissa bytes of tiles first .. first+kGroup-1 (zero where the lane has none).
-__device__ __forceinline__ void load_sm_group(uint2 (&sm)[kGroup], const uint8_t *sm_base, int32_t mine,
-                                              uint32_t first, uint32_t tiles)
-{
-#pragma unroll
-    for (int k = 0; k < kGroup; ++k) {
-        const uint32_t tile = first + k;
-        sm[k] = make_uint2(0u, 0u);
-        if (tile < tiles && mine - static_cast<int32_t>(tile * kTile) > 0)
-            sm[k] = *reinterpret_cast<const uint2 *>(sm_base + tile * kTile);
-    }
-}
-
 // R: symbols per round; kWaves: waves (streams) per workgroup
-template <int R, int kWaves>
-struct Geometry {
-    static constexpr int kIndexBits = R == 4 ? 8 : 12;
-    static constexpr uint32_t kLutEntries = 1u << kIndexBits;
-    static constexpr bool kLutPerWave = R == 4;
-    static constexpr uint32_t kLutWords = kLutEntries / 2 * (kLutPerWave ? kWaves : 1);
-};
-
 template <int R, int kWaves>
 __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
 {
-    using G = Geometry<R, kWaves>;
-    extern __shared__ __align__(16) uint32_t smem[];
+    // Byte tables of the workgroup's tensor, at fixed LDS addresses so that a lookup is one LDS read with
+    // an immediate offset.  With 256 entries a table spans each of the 64 banks once: lanes either read
+    // the same word (broadcast) or different banks, so lookups never conflict.
+    __shared__ __align__(16) uint8_t len_tab[Code<R>::kEntries];
+    __shared__ __align__(16) uint8_t sym_tab[Code<R>::kEntries];
+    extern __shared__ __align__(16) uint32_t stream_lds[];
 
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     // grid: x = workgroup inside the tensor, y = tensor.  The task is copied with one batch of scalar loads.
     const Task t = P.task[blockIdx.y];
-
-    uint16_t *lut = reinterpret_cast<uint16_t *>(smem) + (G::kLutPerWave ? wave * G::kLutEntries : 0);
-    uint32_t *words = smem + G::kLutWords + wave * P.stream_cap_words;
+    uint32_t *words = stream_lds + wave * P.stream_cap_words;
 
     const uint32_t g = blockIdx.x * kWaves + wave;
     bool active = g < t.n_streams;
@@ -179,42 +179,22 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         sn = rest < W ? static_cast<uint32_t>(rest) : W;
         tiles = (sn + kTile - 1) / kTile;
     }
+    const bool full = sn == kGroup * kTile;                        // the common shape: eight whole tiles
     const uint8_t *sm_base = t.blob + t.sm_offset + v0 + lane * 8u;
     const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
 
-    // The sign-mantissa bytes of the first kGroup tiles are requested before anything else: their
-    // addresses need no lookup, and they stay in flight while the stream is staged.
-    uint2 sm[kGroup];
-    load_sm_group(sm, sm_base, mine, 0, tiles);
-
-    // a3: decode table -> LDS, replicated over the index bits above the longest code.  All of a lane's
-    // loads are issued before the first is used.
-    {
-        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.blob + t.lut_offset);
-        const uint32_t mask = (1u << t.max_len) - 1u;
-        if (G::kLutPerWave) {
-            // 256 entries, four per lane
-            const uint32_t i = 4u * lane;
-            const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
-            reinterpret_cast<uint2 *>(lut)[lane] = make_uint2(a | (b << 16), c | (d << 16));
-        } else {
-            // 4096 entries; R = 2 implies max_len >= 9, so any 16 consecutive entries stay consecutive under the mask
-            for (uint32_t i = 16u * threadIdx.x; i < G::kLutEntries; i += 16u * 64u * kWaves) {
-                const uint4 *v = reinterpret_cast<const uint4 *>(src + (i & mask));
-                const uint4 x = v[0], y = v[1];
-                reinterpret_cast<uint4 *>(lut + i)[0] = x;
-                reinterpret_cast<uint4 *>(lut + i)[1] = y;
-            }
-        }
-    }
-
+    uint4 held_a = make_uint4(0u, 0u, 0u, 0u), held_b = held_a;   // first 2 KiB of the stream
+    uint32_t n_held = 0;
     if (active) {
         const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
         const uint64_t ent = t.table[c];
         const uint64_t at = ent & ~15ull;
         mode = static_cast<uint32_t>(ent & 15ull);
         if (mode == ZM_MODE_CODED) {
-            // a4: the stream's words, 128 bits per lane per load
+            // a4: the stream's words, 128 bits per lane per load.  They are requested before the (larger)
+            // sign-mantissa bytes because decoding can not start without them; the first 2 KiB (two
+            // vectors per lane, more than a typical stream) wait in registers until the other requests
+            // are out, longer streams are copied here.
             const uint32_t *offs = reinterpret_cast<const uint32_t *>(t.blob + at + 16);
             uint32_t o0 = 0, o1 = 0;
             const bool head_ok = at + 16 + 4ull * (s + 2) <= t.blob_size;
@@ -225,33 +205,75 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
                 const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
                 const uint4 *src = reinterpret_cast<const uint4 *>(t.blob + at + o0);
                 uint4 *dst = reinterpret_cast<uint4 *>(words);
-                uint32_t i = lane;
-                for (; i + 64 < nvec; i += 128) {
-                    const uint4 a = src[i], b = src[i + 64];
-                    dst[i] = a; dst[i + 64] = b;
-                }
-                if (i < nvec) dst[i] = src[i];
+                n_held = min(nvec, 128u);
+                if (lane < n_held) held_a = src[lane];
+                if (lane + 64 < n_held) held_b = src[lane + 64];
+                for (uint32_t i = 128 + lane; i < nvec; i += 64) dst[i] = src[i];
             }
         } else {
             raw = t.blob + at + static_cast<uint64_t>(s) * W;
             if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.blob_size) active = false;
         }
     }
-    if (G::kLutPerWave) {
-        // LDS written by some lanes of this wave is read by others: order the LDS accesses only
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+    // Next in the request order: the sign-mantissa bytes of the first kGroup tiles.  They stay in flight
+    // while the stream is staged and decoding starts.
+    uint2 sm[kGroup];
+    if (full) {
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
     } else {
-        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            sm[k] = make_uint2(0u, 0u);
+            if (static_cast<uint32_t>(k) < tiles && mine - static_cast<int32_t>(k * kTile) > 0)
+                sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
+        }
     }
+
+    // a3: decode table -> LDS, split into a length table and a symbol table and replicated over the
+    // index bits above the longest code.  Every wave of the workgroup writes the same bytes (LDS word
+    // writes are atomic), so a wave may read as soon as its own writes are done: no workgroup barrier.
+    {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.blob + t.lut_offset);
+        const uint32_t mask = (1u << t.max_len) - 1u;
+        if (R == 4) {
+            // 256 entries, four per lane, all loads issued before the first is used
+            const uint32_t i = 4u * lane;
+            const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
+            const uint32_t ab = a | (b << 16), cd = c | (d << 16);
+            reinterpret_cast<uint32_t *>(sym_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x06040200u);
+            reinterpret_cast<uint32_t *>(len_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x07050301u);
+        } else {
+            // 4096 entries; R = 2 implies max_len >= 9, so any 16 consecutive entries stay consecutive under the mask
+            for (uint32_t i = 16u * lane; i < Code<R>::kEntries; i += 16u * 64u) {
+                const uint4 *v = reinterpret_cast<const uint4 *>(src + (i & mask));
+                const uint4 x = v[0], y = v[1];
+                uint4 sy, le;
+                sy.x = __builtin_amdgcn_perm(x.y, x.x, 0x06040200u); le.x = __builtin_amdgcn_perm(x.y, x.x, 0x07050301u);
+                sy.y = __builtin_amdgcn_perm(x.w, x.z, 0x06040200u); le.y = __builtin_amdgcn_perm(x.w, x.z, 0x07050301u);
+                sy.z = __builtin_amdgcn_perm(y.y, y.x, 0x06040200u); le.z = __builtin_amdgcn_perm(y.y, y.x, 0x07050301u);
+                sy.w = __builtin_amdgcn_perm(y.w, y.z, 0x06040200u); le.w = __builtin_amdgcn_perm(y.w, y.z, 0x07050301u);
+                *reinterpret_cast<uint4 *>(sym_tab + i) = sy;
+                *reinterpret_cast<uint4 *>(len_tab + i) = le;
+            }
+        }
+    }
+
+    if (n_held) {
+        uint4 *dst = reinterpret_cast<uint4 *>(words);
+        if (lane < n_held) dst[lane] = held_a;
+        if (lane + 64 < n_held) dst[lane + 64] = held_b;
+    }
+    // LDS written by some lanes of this wave is read by others: order the LDS accesses only
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
     if (!active) return;
 
     uint16_t *out_base = t.out + v0 + lane * 8u;
 
-    // decoder state
     Decoder<R> dec;
-    dec.lut = lut; dec.words = words; dec.last_word = P.stream_cap_words - 1u;
+    dec.words = words; dec.last_word = P.stream_cap_words - 1u;
     if (mode == ZM_MODE_CODED) {
         const uint2 first = reinterpret_cast<const uint2 *>(words)[lane];
         dec.lo = first.x; dec.hi = first.y;
@@ -259,45 +281,35 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
 
     // Common case, straight-line: a full coded stream of exactly kGroup tiles.  All loads were issued
     // above; from here on the wave only computes and stores.
-    if (mode == ZM_MODE_CODED && sn == kGroup * kTile) {
+    if (mode == ZM_MODE_CODED && full) {
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) {
-            const uint2 ev = dec.tile();
-            uint4 w;
-            recover4(ev.x, sm[k].x, w.x, w.y);
-            recover4(ev.y, sm[k].y, w.z, w.w);
-            store_words(out_base + k * kTile, w);
-        }
+        for (int k = 0; k < kGroup; ++k)
+            recover_and_store(out_base + k * kTile, dec.tile(len_tab, sym_tab), sm[k]);
         return;
     }
+
+    // General case: raw chunks, short last streams, streams of more than kGroup tiles.
     for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
-        uint2 sm_next[kGroup];
-        load_sm_group(sm_next, sm_base, mine, g0 + kGroup, tiles);
+        if (g0) {
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) {
+                sm[k] = make_uint2(0u, 0u);
+                if (g0 + k < tiles && mine - static_cast<int32_t>((g0 + k) * kTile) > 0)
+                    sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (g0 + k) * kTile);
+            }
+        }
 #pragma unroll
         for (int k = 0; k < kGroup; ++k) {
             const uint32_t tile = g0 + k;
             if (tile < tiles) {
                 const int32_t left = mine - static_cast<int32_t>(tile * kTile);
                 uint2 ev = make_uint2(0u, 0u);
-                if (mode == ZM_MODE_CODED) ev = dec.tile();
+                if (mode == ZM_MODE_CODED) ev = dec.tile(len_tab, sym_tab);
                 else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
-                // a8: recovery and store
-                uint4 w;
-                recover4(ev.x, sm[k].x, w.x, w.y);
-                recover4(ev.y, sm[k].y, w.z, w.w);
-                uint16_t *dst = out_base + tile * kTile;
-                if (left >= 8) {
-                    store_words(dst, w);
-                } else if (left > 0) {
-                    const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        if (q < left) dst[q] = static_cast<uint16_t>(ws[q >> 1] >> (16 * (q & 1)));
-                }
+                if (left >= 8) recover_and_store(out_base + tile * kTile, ev, sm[k]);
+                else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, sm[k], left);
             }
         }
-#pragma unroll
-        for (int k = 0; k < kGroup; ++k) sm[k] = sm_next[k];
     }
 }
 
@@ -313,9 +325,8 @@ constexpr size_t kLdsLimit = 64 * 1024;
 template <int R, int kWaves>
 int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
 {
-    using G = Geometry<R, kWaves>;
-    const size_t lds = 4 * (G::kLutWords + kWaves * cap);
-    if (lds > kLdsLimit) {
+    const size_t lds = 4 * kWaves * cap;                       // dynamic part: the streams
+    if (lds + 2 * Code<R>::kEntries > kLdsLimit) {
         if constexpr (kWaves > 1) return launch_tasks<R, kWaves / 2>(L, cap, stream);
         else return ZM_E_ARG;                   // stream too long to stage in LDS
     }
