@@ -62,10 +62,11 @@ struct Launch {
 };
 static_assert(sizeof(Launch) <= 4096, "kernel arguments must stay under 4 KiB");
 
-__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
+// base + number of set bits of `mask` below this lane (the exclusive prefix count of a ballot)
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask, uint32_t base)
 {
     return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
-                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), base));
 }
 
 // Sec. 3.3 recovery of four values at once: e4 and sm4 hold four exponent bytes
@@ -130,21 +131,25 @@ struct Decoder {
                 used += len_tab[idx];
             }
             pos += used;
-            if (R == 4) {
-                e[r] = (s[0] | (s[1] << 8)) | ((s[2] | (s[3] << 8)) << 16);
+            // byte 0 of each symbol register, packed with byte permutes (0x0c selects a zero byte)
+            if constexpr (R == 4) {
+                const uint32_t s01 = __builtin_amdgcn_perm(s[1], s[0], 0x0c0c0400u);
+                e[r] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(s[3], s[2], 0x0c0c0400u), s01, 0x05040100u);
             } else {
-                e[r >> 1] |= (s[0] | (s[1] << 8)) << (16 * (r & 1));
+                const uint32_t s01 = __builtin_amdgcn_perm(s[1], s[0], 0x0c0c0400u);
+                e[r >> 1] = (r & 1) ? __builtin_amdgcn_perm(s01, e[r >> 1], 0x05040100u) : s01;
             }
-            // lanes that crossed a word boundary take the stream's next words, in lane order: the
-            // ballot's prefix count is each taker's offset.  (After the stream's last round the word
-            // read here is never used.)
+            // a6: lanes that crossed a word boundary take the stream's next words, in lane order: the
+            // ballot's prefix count is each taker's offset.  Written without branches (every lane reads
+            // a word, only the takers keep it) so that the whole tile is one basic block.  After the
+            // stream's last round the word read here is never used.
             const bool take = pos >= 32u;
             const uint64_t takers = __ballot(take);
-            if (takers) {
-                const uint32_t idx = min(next + lanes_below(takers), last_word);
-                if (take) { lo = hi; hi = words[idx]; pos -= 32u; }
-                next += static_cast<uint32_t>(__builtin_popcountll(takers));
-            }
+            const uint32_t fresh = words[min(lanes_below(takers, next), last_word)];
+            lo = take ? hi : lo;
+            hi = take ? fresh : hi;
+            pos &= 31u;
+            next += static_cast<uint32_t>(__builtin_popcountll(takers));
         }
         return make_uint2(e[0], e[1]);
     }
