@@ -178,6 +178,29 @@ int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_off
                       const int32_t *expert_ids, int n_selected,
                       void *const *out_bf16, void *stream);
 
+
+/* ---- The paper's own split of the work (Sec. 3.1 step 7, Sec. 3.3): E-chunks
+ * are decompressed by L CPU worker threads, the GPU only runs the recovery
+ * kernel.  These two calls provide that path next to the fused one. ---- */
+
+/* Decompresses E-chunks [chunk_begin, chunk_end) of a blob in host memory into
+ * exponent bytes, one per value, with n_threads worker threads (the paper's L;
+ * values < 1 are taken as 1).  e_out (host) is indexed from the tensor's first
+ * value: chunk c is written to e_out[c*chunk_values ...]; it must hold
+ * n_values bytes.  The blob must have passed zm_validate_blob.
+ * ZM_E_ARG for null pointers or a bad chunk range, ZM_E_FORMAT if the header
+ * or a chunk is malformed, ZM_E_NOMEM. */
+int zm_decode_exponents_host(const void *blob_host, size_t size, uint32_t chunk_begin, uint32_t chunk_end,
+                             uint8_t *e_out, int n_threads);
+
+/* Tensor recovery kernel (Sec. 3.3): merges n_values exponent bytes and
+ * n_values sign-mantissa bytes (both DEVICE, 8-byte aligned) into n_values bf16
+ * words (DEVICE, 16-byte aligned) with vector loads and stores:
+ * word = sign << 15 | exponent << 7 | mantissa.  Asynchronous on `stream`
+ * (a hipStream_t), allocates nothing.  ZM_E_ARG for null or misaligned
+ * pointers, ZM_E_HIP if the launch fails. */
+int zm_recover(const void *exponents, const void *sign_mantissa, size_t n_values, void *out_bf16, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

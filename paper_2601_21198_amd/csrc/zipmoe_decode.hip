@@ -318,6 +318,42 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     }
 }
 
+
+// Stand-alone tensor recovery (Sec. 3.3): one tile of 512 values per wave and step; lane j merges values
+// 8j..8j+7 -- a 64-bit load from each input, one 128-bit store, all contiguous across the wave.
+constexpr int kRecoverTilesPerWave = 8;
+
+__global__ void __launch_bounds__(256) zm_recover_kernel(const uint8_t *__restrict__ e, const uint8_t *__restrict__ sm,
+                                                         uint16_t *__restrict__ out, uint64_t n)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * 4u + (threadIdx.x >> 6);
+    const uint64_t base = wave * (kRecoverTilesPerWave * kTile) + lane * 8u;
+    uint2 ev[kRecoverTilesPerWave], sv[kRecoverTilesPerWave];
+#pragma unroll
+    for (int k = 0; k < kRecoverTilesPerWave; ++k) {
+        const uint64_t i = base + static_cast<uint64_t>(k) * kTile;
+        ev[k] = sv[k] = make_uint2(0u, 0u);
+        if (i + 8 <= n) {
+            ev[k] = *reinterpret_cast<const uint2 *>(e + i);
+            sv[k] = *reinterpret_cast<const uint2 *>(sm + i);
+        } else if (i < n) {                       // the tensor's last, partial group of eight
+            uint32_t eb[2] = {0u, 0u}, sb[2] = {0u, 0u};
+            for (uint32_t q = 0; q < n - i; ++q) {
+                eb[q >> 2] |= static_cast<uint32_t>(e[i + q]) << (8 * (q & 3));
+                sb[q >> 2] |= static_cast<uint32_t>(sm[i + q]) << (8 * (q & 3));
+            }
+            ev[k] = make_uint2(eb[0], eb[1]); sv[k] = make_uint2(sb[0], sb[1]);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kRecoverTilesPerWave; ++k) {
+        const uint64_t i = base + static_cast<uint64_t>(k) * kTile;
+        if (i + 8 <= n) recover_and_store(out + i, ev[k], sv[k]);
+        else if (i < n) recover_and_store_partial(out + i, ev[k], sv[k], static_cast<int32_t>(n - i));
+    }
+}
+
 inline size_t stream_cap_words(uint32_t stream_values, uint32_t max_len_bound)
 {
     const size_t syms = static_cast<size_t>(stream_values / kTile) * 8;
@@ -422,4 +458,19 @@ extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const
     int rc = launch_group<4>(t4, n4, s);
     if (rc != ZM_OK) return rc;
     return launch_group<2>(t2, n2, s);
+}
+
+extern "C" int zm_recover(const void *exponents, const void *sign_mantissa, size_t n_values, void *out_bf16, void *stream)
+{
+    if (n_values == 0) return ZM_OK;
+    if (!exponents || !sign_mantissa || !out_bf16) return ZM_E_ARG;
+    if ((reinterpret_cast<uintptr_t>(exponents) & 7) || (reinterpret_cast<uintptr_t>(sign_mantissa) & 7) ||
+        (reinterpret_cast<uintptr_t>(out_bf16) & 15)) return ZM_E_ARG;
+    const uint64_t per_block = 4ull * kRecoverTilesPerWave * kTile;
+    const uint64_t blocks = (n_values + per_block - 1) / per_block;
+    if (blocks > 0x7FFFFFFFull) return ZM_E_ARG;
+    hipLaunchKernelGGL(zm_recover_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint8_t *>(exponents), static_cast<const uint8_t *>(sign_mantissa),
+                       static_cast<uint16_t *>(out_bf16), static_cast<uint64_t>(n_values));
+    return hipGetLastError() == hipSuccess ? ZM_OK : ZM_E_HIP;
 }

@@ -12,7 +12,9 @@
 #include <array>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 #include <new>
+#include <thread>
 #include <vector>
 
 namespace {
@@ -235,6 +237,81 @@ void package_merge(const std::vector<uint64_t> &weight, int max_len, std::vector
         for (size_t k = 0; k < n; ++k) length[k] = static_cast<uint8_t>(length[k] + level[i].uses[k]);
 }
 
+
+// Table-driven decode of one woven stream on the host: the 64 lanes are walked round by round exactly
+// as the lock-step GPU decoder does, each lane with a 64-bit window over its own two current words.
+// lut: 2^max_len entries (symbol | length << 8).  Returns false if the stream runs out of words.
+bool unweave_stream(const uint32_t *words, size_t n_words, uint32_t n, const uint8_t *lut, uint32_t max_len,
+                    uint8_t *e)
+{
+    const uint32_t R = round_symbols_for(max_len);
+    const uint32_t tiles = (n + kTile - 1) / kTile;
+    const uint32_t rounds = tiles * kRun / R;
+    const uint32_t mask = (1u << max_len) - 1u;
+    if (n_words < 2 * kLanes) return false;
+    uint64_t window[kLanes];      // bits of the lane's stream from its current word on
+    uint32_t pos[kLanes];         // bits of the current word already used
+    for (uint32_t lane = 0; lane < kLanes; ++lane) {
+        window[lane] = words[2 * lane] | (static_cast<uint64_t>(words[2 * lane + 1]) << 32);
+        pos[lane] = 0;
+    }
+    size_t next = 2 * kLanes;
+    for (uint32_t r = 0; r < rounds; ++r) {
+        const uint32_t first_sym = r * R;
+        for (uint32_t lane = 0; lane < kLanes; ++lane) {
+            uint64_t w = window[lane] >> pos[lane];
+            uint32_t p = pos[lane];
+            for (uint32_t k = 0; k < R; ++k) {
+                const uint32_t x = static_cast<uint32_t>(w) & mask;
+                const uint32_t sym = lut[2 * x], len = lut[2 * x + 1];
+                const uint32_t j = first_sym + k;
+                const uint32_t idx = (j / kRun) * kTile + lane * kRun + (j % kRun);
+                if (idx < n) e[idx] = static_cast<uint8_t>(sym);
+                w >>= len; p += len;
+            }
+            pos[lane] = p;
+        }
+        if (r + 1 == rounds) break;
+        for (uint32_t lane = 0; lane < kLanes; ++lane) {
+            if (pos[lane] >= 32) {
+                if (next >= n_words) return false;
+                window[lane] = (window[lane] >> 32) | (static_cast<uint64_t>(words[next++]) << 32);
+                pos[lane] -= 32;
+            }
+        }
+    }
+    return true;
+}
+
+int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, uint64_t c, uint8_t *e_out)
+{
+    const uint64_t ent = load_le<uint64_t>(p + t.table_offset + 8 * c);
+    const uint64_t nxt = load_le<uint64_t>(p + t.table_offset + 8 * (c + 1));
+    const uint64_t at = ent & ~15ull, end = nxt & ~15ull, mode = ent & 15;
+    if (at < t.e_offset || end < at || end > t.blob_size) return ZM_E_FORMAT;
+    const uint64_t first = c * t.chunk_values;
+    const uint32_t cn = static_cast<uint32_t>(std::min<uint64_t>(t.chunk_values, t.n_values - first));
+    uint8_t *e = e_out + first;
+    if (mode == ZM_MODE_RAW) {
+        if (end - at < cn) return ZM_E_FORMAT;
+        std::memcpy(e, p + at, cn);
+        return ZM_OK;
+    }
+    if (mode != ZM_MODE_CODED) return ZM_E_FORMAT;
+    const uint32_t streams = (cn + t.stream_values - 1) / t.stream_values;
+    if (end - at < 16 + 4ull * (streams + 1)) return ZM_E_FORMAT;
+    const uint8_t *h = p + at;
+    for (uint32_t s = 0; s < streams; ++s) {
+        const uint32_t o0 = load_le<uint32_t>(h + 16 + 4 * s), o1 = load_le<uint32_t>(h + 16 + 4 * (s + 1));
+        if ((o0 & 3) || o1 < o0 || o1 > end - at) return ZM_E_FORMAT;
+        const uint32_t sn = std::min(t.stream_values, cn - s * t.stream_values);
+        if (!unweave_stream(reinterpret_cast<const uint32_t *>(h + o0), (o1 - o0) / 4, sn, p + t.lut_offset, t.max_len,
+                            e + static_cast<size_t>(s) * t.stream_values))
+            return ZM_E_FORMAT;
+    }
+    return ZM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -439,6 +516,38 @@ int zm_validate_blob(const void *blob_host, size_t size)
     const uint64_t last = load_le<uint64_t>(p + t.table_offset + 8ull * t.n_chunks);
     if (last != expect || align_up(last, 256) != t.blob_size) return ZM_E_FORMAT;
     return ZM_OK;
+}
+
+
+int zm_decode_exponents_host(const void *blob_host, size_t size, uint32_t chunk_begin, uint32_t chunk_end,
+                             uint8_t *e_out, int n_threads)
+{
+    if (!blob_host || !e_out) return ZM_E_ARG;
+    const uint8_t *p = static_cast<const uint8_t *>(blob_host);
+    zm_tensor_info t;
+    const int rc = read_info(p, size, &t, nullptr);
+    if (rc != ZM_OK) return rc;
+    if (t.blob_size > size) return ZM_E_FORMAT;
+    if (chunk_begin > chunk_end || chunk_end > t.n_chunks) return ZM_E_ARG;
+    if (chunk_begin == chunk_end) return ZM_OK;
+    const uint32_t workers = std::min<uint32_t>(std::max(n_threads, 1), chunk_end - chunk_begin);
+    std::atomic<uint32_t> next_chunk{chunk_begin};
+    std::atomic<int> status{ZM_OK};
+    auto work = [&]() {
+        for (;;) {
+            const uint32_t c = next_chunk.fetch_add(1);
+            if (c >= chunk_end || status.load() != ZM_OK) return;
+            const int r = decode_chunk_exponents(p, t, c, e_out);
+            if (r != ZM_OK) status.store(r);
+        }
+    };
+    try {
+        std::vector<std::thread> pool;
+        for (uint32_t i = 1; i < workers; ++i) pool.emplace_back(work);
+        work();
+        for (auto &th : pool) th.join();
+    } catch (...) { return ZM_E_NOMEM; }
+    return status.load();
 }
 
 }  // extern "C"

@@ -21,7 +21,8 @@ TILE_VALUES = 512
 MODE_CODED, MODE_RAW = 0, 1
 
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
-           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts")
+           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_exponents_host",
+           "zm_recover")
 
 
 class TensorInfo(ctypes.Structure):
@@ -64,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.zm_decode_experts.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.POINTER(TensorInfo),
                                         c.c_int, c.c_int, c.POINTER(c.c_int32), c.c_int,
                                         c.POINTER(c.c_void_p), c.c_void_p]
+        L.zm_decode_exponents_host.argtypes = [c.c_void_p, c.c_size_t, c.c_uint32, c.c_uint32, u8p, c.c_int]
+        L.zm_recover.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
         for name in EXPORTS:
             if name not in ("zm_strerror", "zm_encode_bound"):
                 getattr(L, name).restype = c.c_int
@@ -157,6 +160,27 @@ def decode_experts(blobs, chunk_offsets, infos, n_experts: int, tensors_per_expe
     """zm_decode_experts with ready-made ctypes arrays (see ``ExpertLayer`` for a convenient owner)."""
     _check(lib().zm_decode_experts(blobs, chunk_offsets, infos, n_experts, tensors_per_expert,
                                    expert_ids, n_selected, out_bf16, ctypes.c_void_p(stream)), "zm_decode_experts")
+
+
+def decode_exponents_host(blob, chunk_begin: int = 0, chunk_end: Optional[int] = None, n_threads: int = 1,
+                          out: Optional[np.ndarray] = None) -> np.ndarray:
+    """zm_decode_exponents_host: exponent bytes of chunks [chunk_begin, chunk_end) (default: all)."""
+    b = np.ascontiguousarray(blob, np.uint8)
+    info = blob_info(b[:384])
+    if chunk_end is None:
+        chunk_end = int(info.n_chunks)
+    if out is None:
+        out = np.zeros(int(info.n_values), np.uint8)
+    assert out.dtype == np.uint8 and out.flags.c_contiguous and out.size >= int(info.n_values)
+    _check(lib().zm_decode_exponents_host(b.ctypes.data, b.size, chunk_begin, chunk_end,
+                                          _ptr(out, ctypes.c_uint8), n_threads), "zm_decode_exponents_host")
+    return out
+
+
+def recover(exponents_ptr: int, sign_mantissa_ptr: int, n_values: int, out_ptr: int, stream: int = 0) -> None:
+    """zm_recover on device pointers."""
+    _check(lib().zm_recover(ctypes.c_void_p(exponents_ptr), ctypes.c_void_p(sign_mantissa_ptr), n_values,
+                            ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream)), "zm_recover")
 
 
 class ExpertLayer:

@@ -118,3 +118,48 @@ def test_validate_rejects_damage():
             zm.validate_blob(bad)
     with pytest.raises(zm.ZipMoEError):
         zm.validate_blob(blob[:-256])
+
+
+@pytest.mark.parametrize("kind,max_len", [("gauss", 8), ("wide", 12), ("uniform_u16", 8), ("rare_last", 8), ("all_equal", 8)])
+def test_host_exponent_decoder_matches_reference_split(kind, max_len):
+    """zm_decode_exponents_host (the paper's CPU-side decompression) returns the exponent bytes the
+    reference codec's split gives for the original tensor"""
+    for n in (1, 513, 4096, 3 * 4096 + 77):
+        w = synth.special_tensor(kind, n, seed=n)
+        blob, _ = zm.compress(w, 4096, 1024, max_len)
+        ref_e, ref_sm = zo.split(w)
+        for threads in (1, 3):
+            assert np.array_equal(zm.decode_exponents_host(blob, n_threads=threads), ref_e)
+        # the decoded exponents and the blob's SM section give back the tensor through the reference merge
+        info = zm.blob_info(blob)
+        sm = blob[info.sm_offset: info.sm_offset + n]
+        assert np.array_equal(sm, ref_sm)
+        assert np.array_equal(zo.merge(zm.decode_exponents_host(blob), sm), w)
+
+
+def test_host_exponent_decoder_chunk_ranges_and_errors():
+    w = synth.special_tensor("gauss", 5 * 2048 + 300, seed=8)
+    blob, _ = zm.compress(w, 2048, 512)
+    ref_e, _ = zo.split(w)
+    out = np.full(w.size, 0xEE, np.uint8)
+    zm.decode_exponents_host(blob, 2, 4, n_threads=2, out=out)
+    assert np.array_equal(out[4096:8192], ref_e[4096:8192])
+    assert np.all(out[:4096] == 0xEE) and np.all(out[8192:] == 0xEE)
+    zm.decode_exponents_host(blob, 5, 6, out=out)                      # the short last chunk
+    assert np.array_equal(out[10240:], ref_e[10240:])
+    with pytest.raises(zm.ZipMoEError):
+        zm.decode_exponents_host(blob, 3, 7)
+    with pytest.raises(zm.ZipMoEError):
+        zm.decode_exponents_host(blob, 4, 3)
+    bad = blob.copy()
+    bad[0] ^= 1
+    with pytest.raises(zm.ZipMoEError):
+        zm.decode_exponents_host(bad)
+    with pytest.raises(zm.ZipMoEError):
+        zm.decode_exponents_host(blob[:-256])
+
+
+def test_host_exponent_decoder_on_workload_tensor():
+    w = synth.expert_matrix(synth.CFG2, 0, 0, 1)
+    blob, _ = zm.compress(w, 16384, 4096)
+    assert np.array_equal(zm.decode_exponents_host(blob, n_threads=4), zo.split(w)[0])
