@@ -171,13 +171,34 @@ int zm_validate_blob(const void *blob_host, size_t size);
  * device buffers must stay valid until the stream has passed the call.
  * Blobs must have passed zm_validate_blob: the kernel confines every access to
  * the sizes in `infos`, it does not re-validate the streams.
- * ZM_E_ARG for null pointers, ids out of range, misaligned pointers or a
- * stream length the decoder cannot stage; ZM_E_HIP if a launch fails. */
+ * At most 256 tensors (n_selected * tensors_per_expert) per call.
+ * ZM_E_ARG for null pointers, ids out of range, misaligned pointers, too many
+ * tensors or a stream length the decoder cannot stage; ZM_E_HIP if a launch
+ * fails. */
 int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_offsets,
                       const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
                       const int32_t *expert_ids, int n_selected,
                       void *const *out_bf16, void *stream);
 
+
+/* One tensor given by its parts instead of by one blob, for callers that keep
+ * only some parts of a tensor resident (Sec. 3.2 "Compression States": the
+ * E-chunks and the SM-chunks of an expert may be cached separately).  All four
+ * are DEVICE pointers to verbatim copies of byte ranges of the blob. */
+typedef struct zm_tensor_parts {
+    const void *table;          /* decode table: blob bytes [lut_offset, table_offset); 16-byte aligned  */
+    const void *chunk_offsets;  /* chunk table: blob bytes [table_offset, table_offset + 8*(n_chunks+1)) */
+    const void *sm;             /* SM section: blob bytes [sm_offset, e_offset); 16-byte aligned          */
+    const void *echunks;        /* E-chunks: blob bytes [e_offset, blob_size); 16-byte aligned            */
+} zm_tensor_parts;
+
+/* Same decode as zm_decode_experts for an explicit list of tensors:
+ * parts[i], infos[i] (host arrays) describe tensor i, out_bf16[i] (host array
+ * of DEVICE pointers, 16-byte aligned) receives its n_values bf16 words.
+ * At most 256 tensors per call.  Asynchronous on `stream`, allocates nothing.
+ * ZM_E_ARG for null or misaligned pointers or inconsistent infos; ZM_E_HIP. */
+int zm_decode_tensors(const zm_tensor_parts *parts, const zm_tensor_info *infos, int n_tensors,
+                      void *const *out_bf16, void *stream);
 
 /* ---- The paper's own split of the work (Sec. 3.1 step 7, Sec. 3.3): E-chunks
  * are decompressed by L CPU worker threads, the GPU only runs the recovery

@@ -35,23 +35,25 @@
 
 namespace {
 
-constexpr int kMaxTasks = 48;     // tensors per launch; 72 B each keeps the kernel arguments under 4 KiB
+constexpr int kMaxTasks = 48;     // tensors per launch; 80 B each keeps the kernel arguments under 4 KiB
 constexpr uint32_t kTile = 512;
 constexpr int kGroup = 8;         // tiles whose sign-mantissa loads are in flight together
 
+// One tensor to decode.  Its parts may live in separate allocations (a cache may keep only some of them
+// resident), so each has a pointer of its own.
 struct Task {
-    const uint8_t *blob;
-    const uint64_t *table;
+    const uint8_t *lut;       // decode table: 2^max_len entries of 16 bits
+    const uint8_t *sm;        // sign-mantissa section
+    const uint8_t *echunks;   // E-chunk region (what the blob holds from e_offset on)
+    const uint64_t *table;    // chunk table; its offsets count from the start of the blob
     uint16_t *out;
     uint64_t n_values;
-    uint64_t blob_size;
-    uint64_t sm_offset;
-    uint32_t lut_offset;
+    uint64_t e_offset;        // blob offset of the E-chunk region
+    uint64_t e_size;          // bytes in the E-chunk region
     uint32_t stream_values;
     uint32_t streams_per_chunk;
     uint32_t n_streams;
     uint32_t max_len;
-    uint32_t pad;
 };
 
 struct Launch {
@@ -185,7 +187,7 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         tiles = (sn + kTile - 1) / kTile;
     }
     const bool full = sn == kGroup * kTile;                        // the common shape: eight whole tiles
-    const uint8_t *sm_base = t.blob + t.sm_offset + v0 + lane * 8u;
+    const uint8_t *sm_base = t.sm + v0 + lane * 8u;
     const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
 
     uint4 held_a = make_uint4(0u, 0u, 0u, 0u), held_b = held_a;   // first 2 KiB of the stream
@@ -193,22 +195,24 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     if (active) {
         const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
         const uint64_t ent = t.table[c];
-        const uint64_t at = ent & ~15ull;
+        const uint64_t at = (ent & ~15ull) - t.e_offset;            // offset inside the E-chunk region
         mode = static_cast<uint32_t>(ent & 15ull);
-        if (mode == ZM_MODE_CODED) {
+        if ((ent & ~15ull) < t.e_offset) {
+            active = false;
+        } else if (mode == ZM_MODE_CODED) {
             // a4: the stream's words, 128 bits per lane per load.  They are requested before the (larger)
             // sign-mantissa bytes because decoding can not start without them; the first 2 KiB (two
             // vectors per lane, more than a typical stream) wait in registers until the other requests
             // are out, longer streams are copied here.
-            const uint32_t *offs = reinterpret_cast<const uint32_t *>(t.blob + at + 16);
+            const uint32_t *offs = reinterpret_cast<const uint32_t *>(t.echunks + at + 16);
             uint32_t o0 = 0, o1 = 0;
-            const bool head_ok = at + 16 + 4ull * (s + 2) <= t.blob_size;
+            const bool head_ok = at + 16 + 4ull * (s + 2) <= t.e_size;
             if (head_ok) { o0 = offs[s]; o1 = offs[s + 1]; }
-            if (!head_ok || o1 < o0 || at + o1 > t.blob_size) {
+            if (!head_ok || o1 < o0 || at + o1 > t.e_size) {
                 active = false;
             } else {
                 const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
-                const uint4 *src = reinterpret_cast<const uint4 *>(t.blob + at + o0);
+                const uint4 *src = reinterpret_cast<const uint4 *>(t.echunks + at + o0);
                 uint4 *dst = reinterpret_cast<uint4 *>(words);
                 n_held = min(nvec, 128u);
                 if (lane < n_held) held_a = src[lane];
@@ -216,8 +220,8 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
                 for (uint32_t i = 128 + lane; i < nvec; i += 64) dst[i] = src[i];
             }
         } else {
-            raw = t.blob + at + static_cast<uint64_t>(s) * W;
-            if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.blob_size) active = false;
+            raw = t.echunks + at + static_cast<uint64_t>(s) * W;
+            if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.e_size) active = false;
         }
     }
     // Next in the request order: the sign-mantissa bytes of the first kGroup tiles.  They stay in flight
@@ -239,7 +243,7 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     // index bits above the longest code.  Every wave of the workgroup writes the same bytes (LDS word
     // writes are atomic), so a wave may read as soon as its own writes are done: no workgroup barrier.
     {
-        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.blob + t.lut_offset);
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.lut);
         const uint32_t mask = (1u << t.max_len) - 1u;
         if (R == 4) {
             // 256 entries, four per lane, all loads issued before the first is used
@@ -404,7 +408,59 @@ int launch_group(const Task *tasks, int n, hipStream_t stream)
     return ZM_OK;
 }
 
+
+
+// Checks one tensor's description and appends its task to the group of its round length.
+int add_task(const zm_tensor_parts &pt, const zm_tensor_info &ti, void *out, Task *t4, int &n4, Task *t2, int &n2)
+{
+    if (ti.n_values == 0) return ZM_OK;
+    if (!pt.table || !pt.chunk_offsets || !pt.sm || !pt.echunks || !out) return ZM_E_ARG;
+    if ((reinterpret_cast<uintptr_t>(pt.table) & 15) || (reinterpret_cast<uintptr_t>(pt.chunk_offsets) & 7) ||
+        (reinterpret_cast<uintptr_t>(pt.sm) & 15) || (reinterpret_cast<uintptr_t>(pt.echunks) & 15) ||
+        (reinterpret_cast<uintptr_t>(out) & 15)) return ZM_E_ARG;
+    if (ti.stream_values == 0 || ti.stream_values % kTile || ti.chunk_values % ti.stream_values) return ZM_E_ARG;
+    if (ti.max_len < 1 || ti.max_len > ZM_MAX_CODE_LEN) return ZM_E_ARG;
+    if (ti.round_symbols != (ti.max_len <= 8 ? 4u : 2u)) return ZM_E_ARG;
+    if (ti.e_offset > ti.blob_size || ti.sm_offset + ((ti.n_values + 255) & ~255ull) > ti.e_offset) return ZM_E_ARG;
+    const uint64_t n_streams = (ti.n_values + ti.stream_values - 1) / ti.stream_values;
+    if (n_streams > 0x7FFFFFFFull) return ZM_E_ARG;
+    Task t;
+    t.lut = static_cast<const uint8_t *>(pt.table);
+    t.sm = static_cast<const uint8_t *>(pt.sm);
+    t.echunks = static_cast<const uint8_t *>(pt.echunks);
+    t.table = static_cast<const uint64_t *>(pt.chunk_offsets);
+    t.out = static_cast<uint16_t *>(out);
+    t.n_values = ti.n_values;
+    t.e_offset = ti.e_offset;
+    t.e_size = ti.blob_size - ti.e_offset;
+    t.stream_values = ti.stream_values;
+    t.streams_per_chunk = ti.chunk_values / ti.stream_values;
+    t.n_streams = static_cast<uint32_t>(n_streams);
+    t.max_len = ti.max_len;
+    if (ti.round_symbols == 4) t4[n4++] = t; else t2[n2++] = t;
+    return ZM_OK;
+}
+
+constexpr int kMaxTensorsPerCall = 256;
+
 }  // namespace
+
+extern "C" int zm_decode_tensors(const zm_tensor_parts *parts, const zm_tensor_info *infos, int n_tensors,
+                                 void *const *out_bf16, void *stream)
+{
+    if (n_tensors == 0) return ZM_OK;
+    if (!parts || !infos || !out_bf16 || n_tensors < 0 || n_tensors > kMaxTensorsPerCall) return ZM_E_ARG;
+    Task t4[kMaxTensorsPerCall], t2[kMaxTensorsPerCall];
+    int n4 = 0, n2 = 0;
+    for (int i = 0; i < n_tensors; ++i) {
+        const int rc = add_task(parts[i], infos[i], out_bf16[i], t4, n4, t2, n2);
+        if (rc != ZM_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int rc = launch_group<4>(t4, n4, s);
+    if (rc != ZM_OK) return rc;
+    return launch_group<2>(t2, n2, s);
+}
 
 extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_offsets,
                                  const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
@@ -414,12 +470,8 @@ extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const
     if (n_selected == 0) return ZM_OK;
     if (!blobs || !chunk_offsets || !infos || !expert_ids || !out_bf16) return ZM_E_ARG;
     if (n_experts <= 0 || tensors_per_expert <= 0 || n_selected < 0) return ZM_E_ARG;
-
-    constexpr int kStack = 256;
-    Task stack4[kStack], stack2[kStack];
-    const long total = static_cast<long>(n_selected) * tensors_per_expert;
-    Task *t4 = stack4, *t2 = stack2;
-    if (total > kStack) return ZM_E_ARG;          // more tensors than one MoE layer's selection plausibly has
+    if (static_cast<long>(n_selected) * tensors_per_expert > kMaxTensorsPerCall) return ZM_E_ARG;
+    Task t4[kMaxTensorsPerCall], t2[kMaxTensorsPerCall];
     int n4 = 0, n2 = 0;
     for (int j = 0; j < n_selected; ++j) {
         const int e = expert_ids[j];
@@ -429,33 +481,15 @@ extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const
             const size_t dst = static_cast<size_t>(j) * tensors_per_expert + m;
             const zm_tensor_info &ti = infos[src];
             if (ti.n_values == 0) continue;
-            if (!blobs[src] || !chunk_offsets[src] || !out_bf16[dst]) return ZM_E_ARG;
-            if ((reinterpret_cast<uintptr_t>(blobs[src]) & 15) || (reinterpret_cast<uintptr_t>(out_bf16[dst]) & 15) ||
-                (reinterpret_cast<uintptr_t>(chunk_offsets[src]) & 7)) return ZM_E_ARG;
-            if (ti.stream_values == 0 || ti.stream_values % kTile || ti.chunk_values % ti.stream_values) return ZM_E_ARG;
-            if (ti.max_len < 1 || ti.max_len > ZM_MAX_CODE_LEN || ti.lut_offset > 0xFFFFFFFFull) return ZM_E_ARG;
-            if (ti.round_symbols != (ti.max_len <= 8 ? 4u : 2u)) return ZM_E_ARG;
-            if (ti.sm_offset + ((ti.n_values + 255) & ~255ull) > ti.blob_size) return ZM_E_ARG;
-            const uint64_t n_streams = (ti.n_values + ti.stream_values - 1) / ti.stream_values;
-            if (n_streams > 0x7FFFFFFFull) return ZM_E_ARG;
-            Task t;
-            t.blob = static_cast<const uint8_t *>(blobs[src]);
-            t.table = chunk_offsets[src];
-            t.out = static_cast<uint16_t *>(out_bf16[dst]);
-            t.n_values = ti.n_values;
-            t.blob_size = ti.blob_size;
-            t.sm_offset = ti.sm_offset;
-            t.lut_offset = static_cast<uint32_t>(ti.lut_offset);
-            t.stream_values = ti.stream_values;
-            t.streams_per_chunk = ti.chunk_values / ti.stream_values;
-            t.n_streams = static_cast<uint32_t>(n_streams);
-            t.pad = 0;
-            t.max_len = ti.max_len;
-            if (ti.round_symbols == 4) t4[n4++] = t; else t2[n2++] = t;
+            if (!blobs[src]) return ZM_E_ARG;
+            const uint8_t *blob = static_cast<const uint8_t *>(blobs[src]);
+            const zm_tensor_parts pt{blob + ti.lut_offset, chunk_offsets[src], blob + ti.sm_offset, blob + ti.e_offset};
+            const int rc = add_task(pt, ti, out_bf16[dst], t4, n4, t2, n2);
+            if (rc != ZM_OK) return rc;
         }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    int rc = launch_group<4>(t4, n4, s);
+    const int rc = launch_group<4>(t4, n4, s);
     if (rc != ZM_OK) return rc;
     return launch_group<2>(t2, n2, s);
 }

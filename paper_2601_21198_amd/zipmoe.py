@@ -21,8 +21,8 @@ TILE_VALUES = 512
 MODE_CODED, MODE_RAW = 0, 1
 
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
-           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_exponents_host",
-           "zm_recover")
+           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors",
+           "zm_decode_exponents_host", "zm_recover")
 
 
 class TensorInfo(ctypes.Structure):
@@ -31,6 +31,12 @@ class TensorInfo(ctypes.Structure):
                 ("table_offset", ctypes.c_uint64), ("sm_offset", ctypes.c_uint64), ("e_offset", ctypes.c_uint64),
                 ("chunk_values", ctypes.c_uint32), ("stream_values", ctypes.c_uint32), ("n_chunks", ctypes.c_uint32),
                 ("max_len", ctypes.c_uint32), ("round_symbols", ctypes.c_uint32), ("n_present", ctypes.c_uint32)]
+
+
+class TensorParts(ctypes.Structure):
+    """zm_tensor_parts"""
+    _fields_ = [("table", ctypes.c_void_p), ("chunk_offsets", ctypes.c_void_p), ("sm", ctypes.c_void_p),
+                ("echunks", ctypes.c_void_p)]
 
 
 class ZipMoEError(RuntimeError):
@@ -64,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.zm_validate_blob.argtypes = [c.c_void_p, c.c_size_t]
         L.zm_decode_experts.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.POINTER(TensorInfo),
                                         c.c_int, c.c_int, c.POINTER(c.c_int32), c.c_int,
+                                        c.POINTER(c.c_void_p), c.c_void_p]
+        L.zm_decode_tensors.argtypes = [c.POINTER(TensorParts), c.POINTER(TensorInfo), c.c_int,
                                         c.POINTER(c.c_void_p), c.c_void_p]
         L.zm_decode_exponents_host.argtypes = [c.c_void_p, c.c_size_t, c.c_uint32, c.c_uint32, u8p, c.c_int]
         L.zm_recover.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
@@ -181,6 +189,11 @@ def recover(exponents_ptr: int, sign_mantissa_ptr: int, n_values: int, out_ptr: 
     """zm_recover on device pointers."""
     _check(lib().zm_recover(ctypes.c_void_p(exponents_ptr), ctypes.c_void_p(sign_mantissa_ptr), n_values,
                             ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream)), "zm_recover")
+
+
+def decode_tensors(parts, infos, n_tensors: int, out_bf16, stream: int = 0) -> None:
+    """zm_decode_tensors with ready-made ctypes arrays."""
+    _check(lib().zm_decode_tensors(parts, infos, n_tensors, out_bf16, ctypes.c_void_p(stream)), "zm_decode_tensors")
 
 
 class ExpertLayer:

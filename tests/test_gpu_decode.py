@@ -159,3 +159,30 @@ def test_config3_layer_top8_zipf():
                 assert np.array_equal(g, orig[m].reshape(-1))
                 if ref is not None:
                     assert np.array_equal(g, ref[3 * j + m])
+
+
+def test_decode_tensors_with_parts_in_separate_allocations():
+    """zm_decode_tensors: decode table, chunk table, SM section and E-chunks each in an allocation of its own"""
+    import torch
+    tensors = [synth.special_tensor(k, n, seed=n) for k, n in (("gauss", 3 * 16384 + 700), ("wide", 20000),
+                                                               ("uniform_u16", 9000), ("two_exponents", 4096))]
+    blobs = [zm.compress(w, 16384, 4096, 12 if i == 1 else 8)[0] for i, w in enumerate(tensors)]
+    n = len(blobs)
+    parts, infos, outs = (zm.TensorParts * n)(), (zm.TensorInfo * n)(), (ctypes.c_void_p * n)()
+    keep = []
+    for i, b in enumerate(blobs):
+        info = zm.blob_info(b)
+        infos[i] = info
+        cut = lambda lo, hi: torch.from_numpy(b[lo:hi].copy()).cuda()
+        pieces = [cut(info.lut_offset, info.table_offset), cut(info.table_offset, info.table_offset + 8 * (info.n_chunks + 1)),
+                  cut(info.sm_offset, info.e_offset), cut(info.e_offset, info.blob_size)]
+        out = torch.full((int(info.n_values) + 2 * GUARD,), GUARD_WORD, dtype=torch.int16, device="cuda")
+        keep.append((pieces, out))
+        parts[i] = zm.TensorParts(*[p.data_ptr() for p in pieces])
+        outs[i] = out.data_ptr() + 2 * GUARD
+    zm.decode_tensors(parts, infos, n, ctypes.cast(outs, ctypes.POINTER(ctypes.c_void_p)), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for (pieces, out), w, b in zip(keep, tensors, blobs):
+        a = out.cpu().numpy().view(np.uint16)
+        assert np.all(a[:GUARD] == GUARD_WORD) and np.all(a[-GUARD:] == GUARD_WORD)
+        assert np.array_equal(a[GUARD:-GUARD], zo.decode(b)) and np.array_equal(a[GUARD:-GUARD], w)
