@@ -200,6 +200,80 @@ typedef struct zm_tensor_parts {
 int zm_decode_tensors(const zm_tensor_parts *parts, const zm_tensor_info *infos, int n_tensors,
                       void *const *out_bf16, void *stream);
 
+/* ---- Compression-aware expert cache (Sec. 3.2, Sec. 3.4, Sec. 6) --------------
+ * One cache serves one MoE layer.  HBM is partitioned into four pools, ordered
+ * F < C < S < E: F keeps recovered bf16 tensors, C keeps E-chunks and SM-chunks,
+ * S keeps SM-chunks, E keeps E-chunks.  Whatever an expert's pool does not hold
+ * is fetched from the host copy of its blobs (Sec. 6: host memory is the tier
+ * below device memory) with asynchronous copies that overlap the decode of the
+ * experts that need none.  Every fetch counts one activation of each named
+ * expert; an expert whose rank r in the activation counts (0 = most activated,
+ * ties to the lower id) satisfies r < tau_i = slots[0] + .. + slots[i] +
+ * tolerance is dispatched to the first such pool i (pools of capacity 0 are
+ * skipped); if that pool is better than the one it is in, it moves there, taking
+ * a free slot or evicting the pool's least activated member (never one named by
+ * the same fetch, never one activated more often than itself); an expert that
+ * qualifies for no pool is not kept.  An access never demotes. */
+#define ZM_POOL_FULL       0
+#define ZM_POOL_COMPRESSED 1
+#define ZM_POOL_SM         2
+#define ZM_POOL_E          3
+#define ZM_POOL_NONE       4
+
+typedef struct zm_cache zm_cache;
+
+typedef struct zm_cache_config {
+    int32_t n_experts;
+    int32_t tensors_per_expert;
+    int32_t slots[4];        /* capacities S_F, S_C, S_S, S_E in experts (Sec. 3.4)              */
+    int32_t tolerance;       /* the tolerance margin delta of the rank thresholds (Sec. 3.4)       */
+    int32_t max_selected;    /* most experts one fetch may name; max_selected*tensors_per_expert <= 256 */
+} zm_cache_config;
+
+/* The pool the dispatch rule assigns to `expert` given the activation counts
+ * (host array of n_experts): ZM_POOL_FULL .. ZM_POOL_E, or ZM_POOL_NONE.  A pure
+ * function of its arguments.  ZM_E_ARG (negative) on bad arguments. */
+int zm_cache_dispatch(const uint64_t *counts, int n_experts, const int32_t slots[4], int tolerance, int expert);
+
+/* Bytes of device memory a cache with this configuration needs.  infos: host
+ * array [n_experts * tensors_per_expert] from zm_blob_info. */
+int zm_cache_arena_bytes(const zm_cache_config *config, const zm_tensor_info *infos, size_t *bytes);
+
+/* Creates a cache.  host_blobs: host array [n_experts * tensors_per_expert] of
+ * HOST pointers to the validated blobs (pinned memory makes the copies
+ * asynchronous); they must stay valid for the life of the cache.  arena: DEVICE
+ * memory of at least zm_cache_arena_bytes bytes, 256-byte aligned, owned by the
+ * caller and used by the cache until zm_cache_destroy.  The decode tables and
+ * chunk tables of all tensors are uploaded at once (the call returns when they
+ * are resident); all pools start empty.  The cache creates one HIP stream and two
+ * events of its own and allocates no device memory.
+ * ZM_E_ARG, ZM_E_SIZE (arena too small), ZM_E_NOMEM, ZM_E_HIP. */
+int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs, const zm_tensor_info *infos,
+                    void *arena, size_t arena_bytes, zm_cache **out);
+
+/* Makes the bf16 tensors of the named experts available and tells where they are.
+ *   expert_ids   host array [n_selected] of distinct ids, n_selected <= max_selected
+ *   out_bf16     host array [n_selected * tensors_per_expert], receives DEVICE
+ *                pointers (16-byte aligned) to each tensor's n_values bf16 words
+ *   found_in     optional host array [n_selected]: the pool each expert was found
+ *                in (ZM_POOL_*), before this fetch moved it
+ *   stream       the hipStream_t the caller will read the tensors on
+ * Asynchronous: the tensors are complete once `stream` has passed the call.
+ * Pointers into the F pool stay valid until a later fetch evicts that expert;
+ * all other pointers are valid until the next fetch on this cache.  Work the
+ * caller queued on `stream` before the call (readers of earlier results) is
+ * waited for before anything is overwritten.  Not thread-safe per cache.
+ * ZM_E_ARG for bad ids, duplicates or too many experts; ZM_E_HIP. */
+int zm_cache_fetch(zm_cache *cache, const int32_t *expert_ids, int n_selected, void **out_bf16,
+                   int32_t *found_in, void *stream);
+
+/* The pool `expert` is in now (ZM_POOL_*), or ZM_E_ARG. */
+int zm_cache_pool_of(const zm_cache *cache, int expert);
+
+/* Waits for the cache's own stream, destroys it and the events, frees host
+ * bookkeeping.  The arena goes back to the caller.  NULL is allowed. */
+void zm_cache_destroy(zm_cache *cache);
+
 /* ---- The paper's own split of the work (Sec. 3.1 step 7, Sec. 3.3): E-chunks
  * are decompressed by L CPU worker threads, the GPU only runs the recovery
  * kernel.  These two calls provide that path next to the fused one. ---- */

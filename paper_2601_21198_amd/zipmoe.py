@@ -22,7 +22,9 @@ MODE_CODED, MODE_RAW = 0, 1
 
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
            "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors",
-           "zm_decode_exponents_host", "zm_recover")
+           "zm_decode_exponents_host", "zm_recover", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_create",
+           "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy")
+POOL_FULL, POOL_COMPRESSED, POOL_SM, POOL_E, POOL_NONE = 0, 1, 2, 3, 4
 
 
 class TensorInfo(ctypes.Structure):
@@ -37,6 +39,12 @@ class TensorParts(ctypes.Structure):
     """zm_tensor_parts"""
     _fields_ = [("table", ctypes.c_void_p), ("chunk_offsets", ctypes.c_void_p), ("sm", ctypes.c_void_p),
                 ("echunks", ctypes.c_void_p)]
+
+
+class CacheConfig(ctypes.Structure):
+    """zm_cache_config"""
+    _fields_ = [("n_experts", ctypes.c_int32), ("tensors_per_expert", ctypes.c_int32), ("slots", ctypes.c_int32 * 4),
+                ("tolerance", ctypes.c_int32), ("max_selected", ctypes.c_int32)]
 
 
 class ZipMoEError(RuntimeError):
@@ -75,8 +83,17 @@ def lib() -> ctypes.CDLL:
                                         c.POINTER(c.c_void_p), c.c_void_p]
         L.zm_decode_exponents_host.argtypes = [c.c_void_p, c.c_size_t, c.c_uint32, c.c_uint32, u8p, c.c_int]
         L.zm_recover.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
+        L.zm_cache_dispatch.argtypes = [u64p, c.c_int, c.POINTER(c.c_int32), c.c_int, c.c_int]
+        L.zm_cache_arena_bytes.argtypes = [c.POINTER(CacheConfig), c.POINTER(TensorInfo), c.POINTER(c.c_size_t)]
+        L.zm_cache_create.argtypes = [c.POINTER(CacheConfig), c.POINTER(c.c_void_p), c.POINTER(TensorInfo), c.c_void_p,
+                                      c.c_size_t, c.POINTER(c.c_void_p)]
+        L.zm_cache_fetch.argtypes = [c.c_void_p, c.POINTER(c.c_int32), c.c_int, c.POINTER(c.c_void_p),
+                                     c.POINTER(c.c_int32), c.c_void_p]
+        L.zm_cache_pool_of.argtypes = [c.c_void_p, c.c_int]
+        L.zm_cache_destroy.argtypes = [c.c_void_p]
+        L.zm_cache_destroy.restype = None
         for name in EXPORTS:
-            if name not in ("zm_strerror", "zm_encode_bound"):
+            if name not in ("zm_strerror", "zm_encode_bound", "zm_cache_destroy"):
                 getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -271,3 +288,75 @@ class ExpertLayer:
 
     def decode(self, expert_ids, out_buffers, starts, stream: int = 0) -> None:
         self.make_call(expert_ids, out_buffers, starts)(stream)
+
+
+def cache_dispatch(counts, slots, tolerance: int, expert: int) -> int:
+    """zm_cache_dispatch: the pool the rank rule of Sec. 3.4 assigns to ``expert``."""
+    cnt = np.ascontiguousarray(counts, np.uint64)
+    sl = (ctypes.c_int32 * 4)(*[int(x) for x in slots])
+    rc = lib().zm_cache_dispatch(_ptr(cnt, ctypes.c_uint64), cnt.size, sl, tolerance, expert)
+    if rc < 0:
+        raise ZipMoEError(rc, "zm_cache_dispatch")
+    return rc
+
+
+class ExpertCache:
+    """Owner of one layer's zm_cache: pins the host blobs, allocates the device arena with torch and
+    marshals zm_cache_fetch.  The policy and all data movement are the library's."""
+
+    def __init__(self, expert_blobs: Sequence[Sequence[np.ndarray]], slots, tolerance: int, max_selected: int,
+                 device: str = "cuda:0"):
+        import torch
+        self.n_experts = len(expert_blobs)
+        self.tensors_per_expert = len(expert_blobs[0])
+        n = self.n_experts * self.tensors_per_expert
+        self.infos = (TensorInfo * n)()
+        self.host = []                       # pinned copies of the blobs: the tier below HBM
+        ptrs = (ctypes.c_void_p * n)()
+        k = 0
+        for tensors in expert_blobs:
+            for blob in tensors:
+                validate_blob(blob)
+                self.infos[k] = blob_info(blob[:384])
+                pinned = torch.empty(blob.size, dtype=torch.uint8, pin_memory=True)
+                pinned.numpy()[:] = blob
+                self.host.append(pinned)
+                ptrs[k] = pinned.data_ptr()
+                k += 1
+        self.config = CacheConfig(self.n_experts, self.tensors_per_expert, (ctypes.c_int32 * 4)(*[int(x) for x in slots]),
+                                  tolerance, max_selected)
+        need = ctypes.c_size_t(0)
+        _check(lib().zm_cache_arena_bytes(ctypes.byref(self.config), self.infos, ctypes.byref(need)), "zm_cache_arena_bytes")
+        self.arena = torch.empty(need.value, dtype=torch.uint8, device=device)
+        handle = ctypes.c_void_p()
+        _check(lib().zm_cache_create(ctypes.byref(self.config), ptrs, self.infos, self.arena.data_ptr(), need.value,
+                                     ctypes.byref(handle)), "zm_cache_create")
+        self.handle = handle
+        self.max_selected = max_selected
+
+    def fetch(self, expert_ids, stream: int = 0):
+        """Returns (device pointers [n_selected][tensors_per_expert], pools the experts were found in)."""
+        k = len(expert_ids)
+        ids = (ctypes.c_int32 * k)(*[int(e) for e in expert_ids])
+        outs = (ctypes.c_void_p * (k * self.tensors_per_expert))()
+        found = (ctypes.c_int32 * k)()
+        _check(lib().zm_cache_fetch(self.handle, ids, k, outs, found, ctypes.c_void_p(stream)), "zm_cache_fetch")
+        t = self.tensors_per_expert
+        return [[outs[j * t + m] for m in range(t)] for j in range(k)], list(found)
+
+    def pool_of(self, expert: int) -> int:
+        rc = lib().zm_cache_pool_of(self.handle, expert)
+        if rc < 0:
+            raise ZipMoEError(rc, "zm_cache_pool_of")
+        return rc
+
+    def close(self) -> None:
+        if self.handle:
+            lib().zm_cache_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
