@@ -274,6 +274,55 @@ int zm_cache_pool_of(const zm_cache *cache, int expert);
  * bookkeeping.  The arena goes back to the caller.  NULL is allowed. */
 void zm_cache_destroy(zm_cache *cache);
 
+/* ---- Cache-pool planning (Sec. 3.4 "Hierarchical Cache Planning", App. C, App. D) ----
+ * Host only, double precision.  Ranks are 0-based here: entry 0 of a rank-based
+ * list belongs to the most activated expert. */
+
+/* Profiled delays and shape constants of the makespan estimate (App. C, Alg. 3). */
+typedef struct zm_plan_costs {
+    double decompress_delay;   /* c: decompression of one E-chunk                 */
+    double e_read_delay;       /* v: read of one E-chunk from the tier below      */
+    double sm_read_delay;      /* u: read of one SM-chunk (one tensor's SM bytes) */
+    int32_t threads;           /* L: parallel decompression workers               */
+    int32_t shards_per_tensor; /* K                                               */
+    int32_t tensors_per_expert;/* n                                               */
+} zm_plan_costs;
+
+/* App. D, modified iterative proportional fitting.  f[n]: rank-based inclusion
+ * probabilities (each in [0,1], sum = k).  q_out[n]: selection probabilities of
+ * independent draws whose distribution, conditioned on exactly k selections,
+ * includes rank i with probability f[i].  Starts from weights w = f and
+ * multiplies w_i by f_i / f_i(w) until max |f_i(w) - f_i| < tol or max_iters;
+ * iters_out (may be NULL) receives the iterations used.  ZM_E_ARG, ZM_E_NOMEM. */
+int zm_plan_selection_probabilities(const double *f, int n, int k, int max_iters, double tol, double *q_out, int *iters_out);
+
+/* App. C, Alg. 2: phi_out[h], h = 0..n: probability that exactly h of n
+ * independent selections with probabilities q[n] occur. */
+int zm_plan_hit_distribution(const double *q, int n, double *phi_out);
+
+/* App. C, Alg. 3: estimated makespan of a sparse layer that activates k experts
+ * of which hits[0..3] are found in pools F, C, S, E:
+ * max(SM reads * u + E reads * v, (E reads * v + decompressions * c) / L). */
+int zm_plan_makespan(int k, const int32_t hits[4], const zm_plan_costs *costs, double *makespan_out);
+
+/* Expected makespan when the pools hold the rank intervals of sizes slots[0..3]
+ * one after the other (the remaining ranks are misses), under the hit-pattern
+ * distribution of Sec. 3.4 conditioned on exactly k selections. */
+int zm_plan_expected_makespan(const double *q, int n_experts, const int32_t slots[4], int k, const zm_plan_costs *costs,
+                              double *cost_out);
+
+/* App. C, Alg. 4: grid search over the memory ratios of the pools (step 1/grid,
+ * ratios sum to 1, only pools whose bit is set in pool_mask -- bit 0 = F .. bit 3
+ * = E -- may get memory).  A pool with ratio r holds floor(r * memory_bytes /
+ * bytes_per_expert[pool]) experts, at most the ranks left by the pools before
+ * it.  Configurations are visited in lexicographic order of the (F, C, S, E) grid
+ * counts and replace the best one only if strictly cheaper.  Outputs the best
+ * ratios, their slot counts (ready for zm_cache_config.slots) and the expected
+ * makespan. */
+int zm_plan_pools(const double *f, int n_experts, int k, const zm_plan_costs *costs, double memory_bytes,
+                  const double bytes_per_expert[4], int grid, int pool_mask,
+                  double ratios_out[4], int32_t slots_out[4], double *cost_out);
+
 /* ---- The paper's own split of the work (Sec. 3.1 step 7, Sec. 3.3): E-chunks
  * are decompressed by L CPU worker threads, the GPU only runs the recovery
  * kernel.  These two calls provide that path next to the fused one. ---- */

@@ -23,7 +23,8 @@ MODE_CODED, MODE_RAW = 0, 1
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
            "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors",
            "zm_decode_exponents_host", "zm_recover", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_create",
-           "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy")
+           "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy", "zm_plan_selection_probabilities",
+           "zm_plan_hit_distribution", "zm_plan_makespan", "zm_plan_expected_makespan", "zm_plan_pools")
 POOL_FULL, POOL_COMPRESSED, POOL_SM, POOL_E, POOL_NONE = 0, 1, 2, 3, 4
 
 
@@ -45,6 +46,12 @@ class CacheConfig(ctypes.Structure):
     """zm_cache_config"""
     _fields_ = [("n_experts", ctypes.c_int32), ("tensors_per_expert", ctypes.c_int32), ("slots", ctypes.c_int32 * 4),
                 ("tolerance", ctypes.c_int32), ("max_selected", ctypes.c_int32)]
+
+
+class PlanCosts(ctypes.Structure):
+    """zm_plan_costs"""
+    _fields_ = [("decompress_delay", ctypes.c_double), ("e_read_delay", ctypes.c_double), ("sm_read_delay", ctypes.c_double),
+                ("threads", ctypes.c_int32), ("shards_per_tensor", ctypes.c_int32), ("tensors_per_expert", ctypes.c_int32)]
 
 
 class ZipMoEError(RuntimeError):
@@ -92,6 +99,13 @@ def lib() -> ctypes.CDLL:
         L.zm_cache_pool_of.argtypes = [c.c_void_p, c.c_int]
         L.zm_cache_destroy.argtypes = [c.c_void_p]
         L.zm_cache_destroy.restype = None
+        dp = c.POINTER(c.c_double)
+        L.zm_plan_selection_probabilities.argtypes = [dp, c.c_int, c.c_int, c.c_int, c.c_double, dp, c.POINTER(c.c_int)]
+        L.zm_plan_hit_distribution.argtypes = [dp, c.c_int, dp]
+        L.zm_plan_makespan.argtypes = [c.c_int, c.POINTER(c.c_int32), c.POINTER(PlanCosts), dp]
+        L.zm_plan_expected_makespan.argtypes = [dp, c.c_int, c.POINTER(c.c_int32), c.c_int, c.POINTER(PlanCosts), dp]
+        L.zm_plan_pools.argtypes = [dp, c.c_int, c.c_int, c.POINTER(PlanCosts), c.c_double, dp, c.c_int, c.c_int,
+                                    dp, c.POINTER(c.c_int32), dp]
         for name in EXPORTS:
             if name not in ("zm_strerror", "zm_encode_bound", "zm_cache_destroy"):
                 getattr(L, name).restype = c.c_int
@@ -360,3 +374,48 @@ class ExpertCache:
             self.close()
         except Exception:
             pass
+
+
+def _dbl(a) -> np.ndarray:
+    return np.ascontiguousarray(a, np.float64)
+
+
+def plan_selection_probabilities(f, k: int, max_iters: int = 5000, tol: float = 1e-12):
+    fa = _dbl(f)
+    q = np.zeros(fa.size)
+    it = ctypes.c_int(0)
+    _check(lib().zm_plan_selection_probabilities(_ptr(fa, ctypes.c_double), fa.size, k, max_iters, tol,
+                                                 _ptr(q, ctypes.c_double), ctypes.byref(it)), "zm_plan_selection_probabilities")
+    return q, it.value
+
+
+def plan_hit_distribution(q) -> np.ndarray:
+    qa = _dbl(q)
+    phi = np.zeros(qa.size + 1)
+    _check(lib().zm_plan_hit_distribution(_ptr(qa, ctypes.c_double), qa.size, _ptr(phi, ctypes.c_double)), "zm_plan_hit_distribution")
+    return phi
+
+
+def plan_makespan(k: int, hits, costs: PlanCosts) -> float:
+    out = ctypes.c_double(0)
+    _check(lib().zm_plan_makespan(k, (ctypes.c_int32 * 4)(*hits), ctypes.byref(costs), ctypes.byref(out)), "zm_plan_makespan")
+    return out.value
+
+
+def plan_expected_makespan(q, slots, k: int, costs: PlanCosts) -> float:
+    qa = _dbl(q)
+    out = ctypes.c_double(0)
+    _check(lib().zm_plan_expected_makespan(_ptr(qa, ctypes.c_double), qa.size, (ctypes.c_int32 * 4)(*slots), k,
+                                           ctypes.byref(costs), ctypes.byref(out)), "zm_plan_expected_makespan")
+    return out.value
+
+
+def plan_pools(f, k: int, costs: PlanCosts, memory_bytes: float, bytes_per_expert, grid: int, pool_mask: int = 15):
+    fa, ba = _dbl(f), _dbl(bytes_per_expert)
+    ratios = np.zeros(4)
+    slots = (ctypes.c_int32 * 4)()
+    cost = ctypes.c_double(0)
+    _check(lib().zm_plan_pools(_ptr(fa, ctypes.c_double), fa.size, k, ctypes.byref(costs), memory_bytes,
+                               _ptr(ba, ctypes.c_double), grid, pool_mask, _ptr(ratios, ctypes.c_double), slots,
+                               ctypes.byref(cost)), "zm_plan_pools")
+    return ratios.tolist(), list(slots), cost.value
