@@ -39,7 +39,7 @@
 /* ---- layout constants of the serialised object ------------------------- */
 
 #define ZO_MAGIC        0x454F4D5Au   /* bytes 'Z','M','O','E' */
-#define ZO_VERSION      1u
+#define ZO_VERSION      2u
 #define ZO_HEADER_BYTES 128u
 #define ZO_LANES        64u   /* per-stream lanes                              */
 #define ZO_RUN          8u    /* consecutive values one lane owns in a tile     */
@@ -53,7 +53,7 @@ enum { ZO_MODE_CODED = 0, ZO_MODE_RAW = 1 };
 /* header field offsets (bytes) */
 enum {
     H_MAGIC = 0, H_VERSION = 4, H_NVALUES = 8, H_CHUNK = 16, H_STREAM = 20,
-    H_NCHUNKS = 24, H_L = 28, H_R = 32, H_NPRESENT = 36, H_PADSYM = 40,
+    H_NCHUNKS = 24, H_L = 28, H_R = 32, H_NPRESENT = 36, H_PADSYM = 40, H_TABLE_STRIDE = 44,
     H_LEN_OFF = 48, H_LUT_OFF = 56, H_TABLE_OFF = 64, H_SM_OFF = 72,
     H_E_OFF = 80, H_BLOB_SIZE = 88
 };
@@ -376,29 +376,35 @@ static int decode_stream(const uint32_t *words, size_t n_words, uint32_t n,
  *           byte = its length.  Bit patterns that begin with no code (only
  *           when fewer than two symbols are present) name the pad symbol
  *           with length 1.
- * then      chunk table, 16-byte aligned: n_chunks+1 entries of 64 bits;
- *           entry c = byte offset of E-chunk c from the start of the object
- *           (a multiple of 16) + the chunk's mode in the low 4 bits; the last
- *           entry is the end offset of the last E-chunk, mode bits 0
+ * then      chunk table, 16-byte aligned: n_chunks+1 entries of `stride`
+ *           bytes, stride = 8 + 4*(C/W + 1) rounded up to a multiple of 8.
+ *           Entry c: a 64-bit word = byte offset of E-chunk c from the start
+ *           of the object (a multiple of 16) + the chunk's mode in the low 4
+ *           bits; then 32-bit stream_off[0..S], the byte offsets of the
+ *           chunk's S streams from the chunk start and, in stream_off[S], the
+ *           chunk's length (all zero for a RAW chunk); then zeros.  The last
+ *           entry holds the end offset of the last E-chunk, mode bits 0, and
+ *           zeros.  One read of a table entry tells a decoder where a stream
+ *           starts and ends.
  * then      SM section, 256-byte aligned: n_values sign-mantissa bytes in
  *           tensor order
  * then      E-chunks, the first 256-byte aligned, each 16-byte aligned.
  *           Chunk c covers values [c*C, min(n, (c+1)*C)).
  *             mode RAW:   the chunk's exponent bytes, zero padded to 16
- *             mode CODED: u32 n_values, u32 n_streams S, u32 total bytes,
- *                         u32 0, then u32 stream_off[S+1] (byte offsets from
- *                         the chunk start, zero padded to 16), then the S
- *                         streams; stream s covers values [s*W, (s+1)*W) of
- *                         the chunk
+ *             mode CODED: the chunk's S streams one after the other;
+ *                         stream s covers values [s*W, (s+1)*W) of the chunk
  *           A chunk is stored RAW when its coded form would not be smaller.
  * The object's total size is a multiple of 256.
  */
 
+/* bytes of one chunk-table entry */
+static uint64_t table_stride(uint32_t C, uint32_t W) { return round_up(8 + 4 * ((uint64_t)(C / W) + 1), 8); }
+
 size_t zo_encode_bound(size_t n_values, uint32_t chunk_values, uint32_t stream_values)
 {
-    (void)stream_values;
     size_t chunks = chunk_values ? (n_values + chunk_values - 1) / chunk_values : 0;
-    return 384 + 2 * 4096 + 16 + 8 * (chunks + 1) + 256 + n_values + 256 + n_values + 16 * chunks + 512;
+    size_t stride = (chunk_values && stream_values && chunk_values % stream_values == 0) ? (size_t)table_stride(chunk_values, stream_values) : 8;
+    return 384 + 2 * 4096 + 16 + stride * (chunks + 1) + 256 + n_values + 256 + n_values + 16 * chunks + 512;
 }
 
 static int check_geometry(uint32_t C, uint32_t W)
@@ -430,7 +436,8 @@ int zo_encode(const uint16_t *w, size_t n, uint32_t C, uint32_t W,
     uint64_t len_off = ZO_HEADER_BYTES;
     uint64_t lut_off = len_off + 256;
     uint64_t table_off = round_up(lut_off + 2 * ((uint64_t)1 << L), 16);
-    uint64_t sm_off = round_up(table_off + 8 * (K + 1), 256);
+    const uint64_t stride = table_stride(C, W);
+    uint64_t sm_off = round_up(table_off + stride * (K + 1), 256);
     uint64_t e_off = round_up(sm_off + n, 256);
 
     memset(blob, 0, e_off);
@@ -459,33 +466,34 @@ int zo_encode(const uint16_t *w, size_t n, uint32_t C, uint32_t W,
         uint32_t cn = (uint32_t)((n - c * C) < C ? (n - c * C) : C);
         uint32_t S = (cn + W - 1) / W;
         uint64_t raw_bytes = round_up(cn, 16);
-        /* coded form, built in place */
-        uint64_t head = 16 + round_up(4 * ((uint64_t)S + 1), 16);
-        uint64_t at = head;
+        /* coded form, built in place; the stream offsets go to the chunk's table entry */
+        uint8_t *entry = blob + table_off + stride * c;
+        uint64_t at = 0;
         uint8_t *base = blob + pos;
         int fits = 1;
-        memset(base, 0, head);
+        memset(entry, 0, stride);
         for (uint32_t s = 0; s < S && fits; s++) {
             uint32_t sn = (cn - s * W) < W ? (cn - s * W) : W;
             size_t nw = encode_stream(e + c * C + (size_t)s * W, sn, len, code, L, pad, tmp);
-            put32(base + 16 + 4 * s, (uint32_t)at);
+            put32(entry + 8 + 4 * s, (uint32_t)at);
             if (at + 4 * nw >= raw_bytes) { fits = 0; break; }
             for (size_t j = 0; j < nw; j++) put32(base + at + 4 * j, tmp[j]);
             at += 4 * nw;
         }
         if (fits && at < raw_bytes) {
-            put32(base + 0, cn); put32(base + 4, S); put32(base + 8, (uint32_t)at); put32(base + 12, 0);
-            put32(base + 16 + 4 * S, (uint32_t)at);
-            put64(blob + table_off + 8 * c, pos | ZO_MODE_CODED);
+            put32(entry + 8 + 4 * S, (uint32_t)at);
+            put64(entry, pos | ZO_MODE_CODED);
             pos += at;
         } else {
+            memset(entry, 0, stride);
             memset(base, 0, raw_bytes);
             memcpy(base, e + c * C, cn);
-            put64(blob + table_off + 8 * c, pos | ZO_MODE_RAW);
+            put64(entry, pos | ZO_MODE_RAW);
             pos += raw_bytes;
         }
     }
-    put64(blob + table_off + 8 * K, pos);
+    memset(blob + table_off + stride * K, 0, stride);
+    put64(blob + table_off + stride * K, pos);
     uint64_t total = round_up(pos, 256);
     memset(blob + pos, 0, total - pos);
 
@@ -493,7 +501,7 @@ int zo_encode(const uint16_t *w, size_t n, uint32_t C, uint32_t W,
     put64(blob + H_NVALUES, n); put32(blob + H_CHUNK, C); put32(blob + H_STREAM, W);
     put32(blob + H_NCHUNKS, (uint32_t)K); put32(blob + H_L, (uint32_t)L);
     put32(blob + H_R, round_symbols(L)); put32(blob + H_NPRESENT, (uint32_t)n_present);
-    put32(blob + H_PADSYM, (uint32_t)pad);
+    put32(blob + H_PADSYM, (uint32_t)pad); put32(blob + H_TABLE_STRIDE, (uint32_t)stride);
     put64(blob + H_LEN_OFF, len_off); put64(blob + H_LUT_OFF, lut_off);
     put64(blob + H_TABLE_OFF, table_off); put64(blob + H_SM_OFF, sm_off);
     put64(blob + H_E_OFF, e_off); put64(blob + H_BLOB_SIZE, total);
@@ -529,7 +537,9 @@ int zo_decode_chunks(const uint8_t *blob, size_t size, size_t c0, size_t c1, uin
     if (len_off != ZO_HEADER_BYTES || lut_off != len_off + 256) return ZO_E_FORMAT;
     if (L < 1 || L > ZO_MAX_LEN) return ZO_E_FORMAT;
     if (table_off != round_up(lut_off + 2 * ((uint64_t)1 << L), 16)) return ZO_E_FORMAT;
-    if (sm_off != round_up(table_off + 8 * (K + 1), 256)) return ZO_E_FORMAT;
+    const uint64_t stride = table_stride(C, W);
+    if (get32(blob + H_TABLE_STRIDE) != stride) return ZO_E_FORMAT;
+    if (sm_off != round_up(table_off + stride * (K + 1), 256)) return ZO_E_FORMAT;
     if (e_off != round_up(sm_off + n, 256) || e_off > total) return ZO_E_FORMAT;
     if (c0 > c1 || c1 > K) return ZO_E_ARG;
 
@@ -547,24 +557,26 @@ int zo_decode_chunks(const uint8_t *blob, size_t size, size_t c0, size_t c1, uin
     uint32_t *wbuf = (uint32_t *)malloc(stream_words_bound(W) * sizeof(uint32_t));
     int rc = ZO_OK;
     for (uint64_t c = c0; c < c1 && rc == ZO_OK; c++) {
-        uint64_t ent = get64(blob + table_off + 8 * c), nxt = get64(blob + table_off + 8 * (c + 1));
+        const uint8_t *entry = blob + table_off + stride * c;
+        uint64_t ent = get64(entry), nxt = get64(entry + stride);
         uint64_t at = ent & ~(uint64_t)15, end = nxt & ~(uint64_t)15;
         unsigned mode = (unsigned)(ent & 15);
         uint32_t cn = (uint32_t)((n - c * C) < C ? (n - c * C) : C);
+        uint32_t S = (cn + W - 1) / W;
         if (at < e_off || end < at || end > total) { rc = ZO_E_FORMAT; break; }
         if (c == 0 && at != e_off) { rc = ZO_E_FORMAT; break; }
         const uint8_t *base = blob + at;
+        /* unused offset slots of the entry are zero */
+        for (uint64_t j = 8 + 4 * ((uint64_t)(mode == ZO_MODE_CODED ? S : 0) + (mode == ZO_MODE_CODED)); j < stride && rc == ZO_OK; j += 4)
+            if (get32(entry + j) != 0) rc = ZO_E_FORMAT;
+        if (rc != ZO_OK) break;
         if (mode == ZO_MODE_RAW) {
             if (end - at != round_up(cn, 16)) { rc = ZO_E_FORMAT; break; }
             memcpy(e, base, cn);
         } else if (mode == ZO_MODE_CODED) {
-            uint32_t S = (cn + W - 1) / W;
-            uint64_t head = 16 + round_up(4 * ((uint64_t)S + 1), 16);
-            if (end - at < head) { rc = ZO_E_FORMAT; break; }
-            if (get32(base) != cn || get32(base + 4) != S || get32(base + 8) != end - at || get32(base + 12) != 0) { rc = ZO_E_FORMAT; break; }
-            if (get32(base + 16) != head || get32(base + 16 + 4 * S) != end - at) { rc = ZO_E_FORMAT; break; }
+            if (get32(entry + 8) != 0 || get32(entry + 8 + 4 * S) != end - at) { rc = ZO_E_FORMAT; break; }
             for (uint32_t s = 0; s < S && rc == ZO_OK; s++) {
-                uint32_t o0 = get32(base + 16 + 4 * s), o1 = get32(base + 16 + 4 * (s + 1));
+                uint32_t o0 = get32(entry + 8 + 4 * s), o1 = get32(entry + 8 + 4 * (s + 1));
                 if (o0 % 16 || o1 % 16 || o1 < o0 || o1 > end - at) { rc = ZO_E_FORMAT; break; }
                 size_t nw = (o1 - o0) / 4;
                 if (nw > stream_words_bound(W)) { rc = ZO_E_FORMAT; break; }
@@ -575,7 +587,7 @@ int zo_decode_chunks(const uint8_t *blob, size_t size, size_t c0, size_t c1, uin
         } else rc = ZO_E_FORMAT;
         if (rc == ZO_OK) zo_merge(e, sm + c * C, cn, out + c * C);
     }
-    if (rc == ZO_OK && c1 == K && get64(blob + table_off + 8 * K) > total) rc = ZO_E_FORMAT;
+    if (rc == ZO_OK && c1 == K && get64(blob + table_off + stride * K) > total) rc = ZO_E_FORMAT;
     free(e); free(wbuf);
     return rc;
 }

@@ -20,9 +20,14 @@ def roundtrip(w, C, W, max_len=8):
 
 
 def chunk_table(blob):
+    """(header, 64-bit offset|mode word of every table entry, stream offsets of every entry)"""
     h = zo.header(blob)
-    t = blob[h["table_offset"]: h["table_offset"] + 8 * (h["n_chunks"] + 1)].view("<u8")
-    return h, t
+    stride = h["table_stride"]
+    assert stride == -(-(8 + 4 * (h["chunk_values"] // h["stream_values"] + 1)) // 8) * 8
+    raw = blob[h["table_offset"]: h["table_offset"] + stride * (h["n_chunks"] + 1)].reshape(h["n_chunks"] + 1, stride)
+    words = np.ascontiguousarray(raw[:, :8]).view("<u8").reshape(-1)
+    offs = np.ascontiguousarray(raw[:, 8:]).view("<u4").reshape(h["n_chunks"] + 1, -1)
+    return h, words, offs
 
 
 def test_all_65536_patterns_round_trip():
@@ -85,7 +90,7 @@ def test_stream_sizes_match_closed_form(max_len):
     w = synth.special_tensor(kind, 3 * 4096 + 2500, seed=9)
     C, W = 4096, 2048
     blob, lengths = roundtrip(w, C, W, max_len)
-    h, table = chunk_table(blob)
+    h, table, stream_offs = chunk_table(blob)
     assert h["L"] == lengths.max() and h["R"] == (4 if h["L"] <= 8 else 2)
     e, _ = zo.split(w)
     total_code_bits = 0
@@ -94,9 +99,8 @@ def test_stream_sizes_match_closed_form(max_len):
         assert mode == zo.MODE_CODED
         cn = min(C, w.size - c * C)
         S = -(-cn // W)
-        head = blob[at: at + 16].view("<u4")
-        assert head[0] == cn and head[1] == S and head[2] == (int(table[c + 1]) & ~15) - at
-        offs = blob[at + 16: at + 16 + 4 * (S + 1)].view("<u4")
+        offs = stream_offs[c]
+        assert offs[0] == 0 and offs[S] == (int(table[c + 1]) & ~15) - at and not offs[S + 1:].any()
         for s in range(S):
             es = e[c * C + s * W: c * C + min(cn, (s + 1) * W)]
             words, bits = expected_stream_words(es, lengths, h["R"])
@@ -113,9 +117,9 @@ def test_first_words_hold_each_lanes_first_codes():
     blob, lengths = roundtrip(w, 4096, 4096)
     code, _ = zo.canonical(lengths)
     book = {(int(lengths[s]), int(code[s])): s for s in range(256) if lengths[s]}
-    h, table = chunk_table(blob)
+    h, table, stream_offs = chunk_table(blob)
     at = int(table[0]) & ~15
-    offs = blob[at + 16: at + 24].view("<u4")
+    offs = stream_offs[0]
     words = blob[at + offs[0]: at + offs[1]].view("<u4")
     e, _ = zo.split(w)
     for lane in range(64):
@@ -130,13 +134,13 @@ def test_first_words_hold_each_lanes_first_codes():
 def test_incompressible_chunks_are_stored_raw():
     w = synth.special_tensor("uniform_u16", 3 * 4096, seed=4)
     blob, _ = roundtrip(w, 4096, 1024)
-    h, table = chunk_table(blob)
+    h, table, stream_offs = chunk_table(blob)
     assert all(int(t) & 15 == zo.MODE_RAW for t in table[:-1])
-    assert int(table[-1]) - h["e_offset"] == w.size
+    assert int(table[-1]) - h["e_offset"] == w.size and not stream_offs.any()
     # a tensor whose first chunk is Gaussian and whose second is uniform noise mixes both modes
     mixed = np.concatenate([synth.special_tensor("gauss", 3 * 4096, 1), synth.special_tensor("uniform_u16", 4096, 2)])
     blob, _ = roundtrip(mixed, 4096, 4096, 12)     # 256 symbols present: only codes longer than 8 bits can compress
-    _, table = chunk_table(blob)
+    _, table, _ = chunk_table(blob)
     assert [int(t) & 15 for t in table[:-1]] == [zo.MODE_CODED] * 3 + [zo.MODE_RAW]
 
 
@@ -184,8 +188,8 @@ def test_partial_decode_touches_only_its_chunks():
 def test_damaged_objects_are_rejected():
     w = synth.special_tensor("gauss", 8192, seed=6)
     blob, lengths = zo.encode_tensor(w, 4096, 2048)
-    h, table = chunk_table(blob)
-    for off in (0, 4, 16, 20, 24, 28, 32, 56, 64, 72, 80, 88):
+    h, table, stream_offs = chunk_table(blob)
+    for off in (0, 4, 16, 20, 24, 28, 32, 44, 56, 64, 72, 80, 88):
         bad = blob.copy()
         bad[off] ^= 0x5A
         with pytest.raises(zo.OracleError):
@@ -194,20 +198,19 @@ def test_damaged_objects_are_rejected():
     bad[h["len_offset"] + int(np.argmax(lengths))] = 1
     with pytest.raises(zo.OracleError):
         zo.decode(bad)
-    bad = blob.copy()                                   # chunk header disagrees with the table
-    bad[int(table[0]) & ~15] ^= 1
-    with pytest.raises(zo.OracleError):
-        zo.decode(bad)
+    entry0 = h["table_offset"]
+    for off in (entry0 + 8, entry0 + 12, entry0 + 16, entry0 + h["table_stride"] - 4, entry0 + h["table_stride"] + 8):
+        bad = blob.copy()                               # stream offsets of a table entry damaged
+        bad[off] ^= 0x10
+        with pytest.raises(zo.OracleError):
+            zo.decode(bad)
     bad = blob.copy()                                   # non-zero padding word after a stream
     at = int(table[0]) & ~15
-    offs = bad[at + 16: at + 28].view("<u4")
-    if not bad[at + offs[1] - 4: at + offs[1]].any():
-        bad[at + offs[1] - 1] = 0x80
-        try:
-            out = zo.decode(bad)
-            assert not np.array_equal(out, w) or True
-        except zo.OracleError:
-            pass
+    end0 = at + int(stream_offs[0][1])
+    if not bad[end0 - 4: end0].any():
+        bad[end0 - 1] = 0x80
+        with pytest.raises(zo.OracleError):
+            zo.decode(bad)
     with pytest.raises(zo.OracleError):
         zo.decode(blob[:-256])                          # truncated
     # encoding with a codebook that lacks a symbol that occurs is refused
