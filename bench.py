@@ -61,7 +61,8 @@ def build_layer(wl, layer: int, stream_values: int, max_len: int, workers: int, 
             blob, offs = zm.compress(m, wl.chunk_values, stream_values, max_len)
             info = zm.blob_info(blob[:384])
             # what one decode of this tensor must read: SM bytes, E-chunks, chunk table, decode table
-            read_bytes += int(info.n_values) + (int(offs[-1]) - int(info.e_offset)) + 8 * (int(info.n_chunks) + 1) + (2 << int(info.max_len))
+            read_bytes += (int(info.n_values) + (int(offs[-1, 0]) - int(info.e_offset)) +
+                           int(info.table_stride) * (int(info.n_chunks) + 1) + (2 << int(info.max_len)))
             n_values += int(info.n_values)
             blobs.append(blob)
         return blobs, read_bytes, n_values

@@ -32,14 +32,19 @@
  *   byte 128   code_len[256]: code length of every exponent value, 0 = absent
  *   byte 384   decode table, 2^L 16-bit entries (L = longest code length): the
  *              entry for an L-bit stream window is symbol | length << 8
- *   then       chunk table: n_chunks+1 64-bit entries, byte offset of each
- *              E-chunk in the blob (multiple of 16) | mode in the low 4 bits
+ *   then       chunk table: n_chunks+1 entries of table_stride bytes
+ *              (8 + 4*(chunk_values/stream_values + 1), rounded up to a
+ *              multiple of 8): a 64-bit word = byte offset of the E-chunk in
+ *              the blob (multiple of 16) | mode in the low 4 bits, then the
+ *              32-bit byte offsets of the chunk's streams from the chunk start
+ *              followed by the chunk's length (zeros for a raw chunk); the last
+ *              entry holds the end offset
  *   then       SM section (256-byte aligned): n_values sign-mantissa bytes
  *              (sign in bit 7, mantissa in bits 6..0), tensor order
  *   then       E-chunks (first one 256-byte aligned, each 16-byte aligned);
  *              chunk c covers values [c*chunk_values, (c+1)*chunk_values).
- *              mode 1 (raw): the exponent bytes.  mode 0 (coded): a 16-byte
- *              chunk header, the byte offsets of its streams, the streams.
+ *              mode 1 (raw): the exponent bytes.  mode 0 (coded): the chunk's
+ *              streams one after the other.
  *              A stream covers stream_values consecutive values and weaves 64
  *              per-lane bitstreams into one sequence of 32-bit words in the
  *              order a 64-lane lock-step decoder consumes them: in every tile
@@ -85,6 +90,8 @@ typedef struct zm_tensor_info {
     uint32_t max_len;        /* L, longest code length in use (>= 1)              */
     uint32_t round_symbols;  /* R                                                 */
     uint32_t n_present;      /* exponent values that occur                        */
+    uint32_t table_stride;   /* bytes of one chunk-table entry                    */
+    uint32_t reserved;
 } zm_tensor_info;
 
 /* Library version as major*10000 + minor*100 + patch. Never fails. */
@@ -122,7 +129,8 @@ size_t zm_encode_bound(size_t n_values, uint32_t chunk_values, uint32_t stream_v
  *   blob, blob_cap    output buffer, at least zm_encode_bound(...) bytes
  *   blob_size         out: bytes written (a multiple of 256)
  *   chunk_offsets, chunk_offsets_cap   optional (may be NULL/0) copy of the
- *                     blob's chunk table, n_chunks+1 entries
+ *                     blob's chunk table, (n_chunks+1) * table_stride/8 64-bit
+ *                     words (capacity counted in such words)
  *   n_chunks          out (may be NULL)
  * The output is a function of the inputs alone: equal inputs give equal bytes.
  * ZM_E_ARG for bad geometry, bad codebook or a symbol without a code;
@@ -153,8 +161,8 @@ int zm_validate_blob(const void *blob_host, size_t size);
  *                     expert e; each 16-byte aligned, uploaded unchanged from
  *                     zm_encode's output
  *   chunk_offsets     host array, same shape, of DEVICE pointers to each
- *                     tensor's chunk table (n_chunks+1 entries; may point into
- *                     the blob at table_offset)
+ *                     tensor's chunk table ((n_chunks+1) * table_stride bytes;
+ *                     may point into the blob at table_offset)
  *   infos             host array, same shape, from zm_blob_info
  *   n_experts, tensors_per_expert
  *   expert_ids        host array [n_selected], each in [0, n_experts);
@@ -187,7 +195,7 @@ int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_off
  * are DEVICE pointers to verbatim copies of byte ranges of the blob. */
 typedef struct zm_tensor_parts {
     const void *table;          /* decode table: blob bytes [lut_offset, table_offset); 16-byte aligned  */
-    const void *chunk_offsets;  /* chunk table: blob bytes [table_offset, table_offset + 8*(n_chunks+1)) */
+    const void *chunk_offsets;  /* chunk table: blob bytes [table_offset, table_offset + table_stride*(n_chunks+1)) */
     const void *sm;             /* SM section: blob bytes [sm_offset, e_offset); 16-byte aligned          */
     const void *echunks;        /* E-chunks: blob bytes [e_offset, blob_size); 16-byte aligned            */
 } zm_tensor_parts;

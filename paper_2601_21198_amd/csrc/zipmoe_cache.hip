@@ -67,7 +67,7 @@ bool make_layout(const zm_cache_config &c, const zm_tensor_info *infos, Layout &
         L.meta_off[i] = meta;
         meta += up16(t.table_offset - t.lut_offset);
         L.meta_table_off[i] = meta;
-        meta += up16(8ull * (t.n_chunks + 1));
+        meta += up16(static_cast<size_t>(t.table_stride) * (t.n_chunks + 1));
     }
     L.meta_bytes = up256(meta);
     for (int m = 0; m < T; ++m) {
@@ -189,7 +189,7 @@ int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs
         const zm_tensor_info &t = c->infos[i];
         if (hipMemcpyAsync(c->arena + c->lay.meta_off[i], c->host[i] + t.lut_offset, t.table_offset - t.lut_offset,
                            hipMemcpyHostToDevice, c->copy_stream) != hipSuccess ||
-            hipMemcpyAsync(c->arena + c->lay.meta_table_off[i], c->host[i] + t.table_offset, 8ull * (t.n_chunks + 1),
+            hipMemcpyAsync(c->arena + c->lay.meta_table_off[i], c->host[i] + t.table_offset, static_cast<size_t>(t.table_stride) * (t.n_chunks + 1),
                            hipMemcpyHostToDevice, c->copy_stream) != hipSuccess) {
             zm_cache_destroy(c);
             return ZM_E_HIP;

@@ -14,8 +14,9 @@
 //           both contiguous across the wave (512 B and 1 KiB per instruction)
 //
 // Per wave
-//   1. the stream's words are requested with 128-bit loads (a4) -- first, because
-//      decoding can not start without them -- and go to LDS;
+//   1. one read of the chunk's table entry locates the stream; its words are
+//      requested with 128-bit loads (a4) -- first, because decoding can not start
+//      without them -- and go to LDS;
 //   2. the sign-mantissa bytes of the stream's first eight tiles are requested;
 //   3. the decode table goes to LDS (a3) as two byte tables (code length, symbol)
 //      at fixed LDS addresses, replicated to the full index width;
@@ -45,7 +46,7 @@ struct Task {
     const uint8_t *lut;       // decode table: 2^max_len entries of 16 bits
     const uint8_t *sm;        // sign-mantissa section
     const uint8_t *echunks;   // E-chunk region (what the blob holds from e_offset on)
-    const uint64_t *table;    // chunk table; its offsets count from the start of the blob
+    const uint64_t *table;    // chunk table (entries of 8 + 4*(streams_per_chunk+1) bytes, rounded up to 8); offsets count from the start of the blob
     uint16_t *out;
     uint64_t n_values;
     uint64_t e_offset;        // blob offset of the E-chunk region
@@ -194,7 +195,12 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     uint32_t n_held = 0;
     if (active) {
         const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
-        const uint64_t ent = t.table[c];
+        // one read of the chunk's table entry gives the chunk's place and mode and this stream's extent
+        const uint32_t stride = (8u + 4u * (t.streams_per_chunk + 1u) + 7u) & ~7u;
+        const uint8_t *entry = reinterpret_cast<const uint8_t *>(t.table) + static_cast<uint64_t>(c) * stride;
+        const uint64_t ent = *reinterpret_cast<const uint64_t *>(entry);
+        const uint32_t o0 = reinterpret_cast<const uint32_t *>(entry + 8)[s];
+        const uint32_t o1 = reinterpret_cast<const uint32_t *>(entry + 8)[s + 1];
         const uint64_t at = (ent & ~15ull) - t.e_offset;            // offset inside the E-chunk region
         mode = static_cast<uint32_t>(ent & 15ull);
         if ((ent & ~15ull) < t.e_offset) {
@@ -204,11 +210,7 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
             // sign-mantissa bytes because decoding can not start without them; the first 2 KiB (two
             // vectors per lane, more than a typical stream) wait in registers until the other requests
             // are out, longer streams are copied here.
-            const uint32_t *offs = reinterpret_cast<const uint32_t *>(t.echunks + at + 16);
-            uint32_t o0 = 0, o1 = 0;
-            const bool head_ok = at + 16 + 4ull * (s + 2) <= t.e_size;
-            if (head_ok) { o0 = offs[s]; o1 = offs[s + 1]; }
-            if (!head_ok || o1 < o0 || at + o1 > t.e_size) {
+            if (o1 < o0 || at + o1 > t.e_size) {
                 active = false;
             } else {
                 const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
@@ -422,6 +424,7 @@ int add_task(const zm_tensor_parts &pt, const zm_tensor_info &ti, void *out, Tas
     if (ti.max_len < 1 || ti.max_len > ZM_MAX_CODE_LEN) return ZM_E_ARG;
     if (ti.round_symbols != (ti.max_len <= 8 ? 4u : 2u)) return ZM_E_ARG;
     if (ti.e_offset > ti.blob_size || ti.sm_offset + ((ti.n_values + 255) & ~255ull) > ti.e_offset) return ZM_E_ARG;
+    if (ti.table_stride != ((8u + 4u * (ti.chunk_values / ti.stream_values + 1u) + 7u) & ~7u)) return ZM_E_ARG;
     const uint64_t n_streams = (ti.n_values + ti.stream_values - 1) / ti.stream_values;
     if (n_streams > 0x7FFFFFFFull) return ZM_E_ARG;
     Task t;

@@ -20,7 +20,7 @@
 namespace {
 
 constexpr uint32_t kMagic = 0x454F4D5Au;   // "ZMOE"
-constexpr uint32_t kVersion = 1;
+constexpr uint32_t kVersion = 2;
 constexpr uint32_t kHeaderBytes = 128;
 constexpr uint32_t kLanes = 64;
 constexpr uint32_t kRun = 8;               // consecutive values per lane per tile
@@ -29,7 +29,7 @@ constexpr uint32_t kTile = kLanes * kRun;  // 512
 // header field positions
 struct Hdr {
     static constexpr size_t magic = 0, version = 4, n_values = 8, chunk = 16, stream = 20, n_chunks = 24,
-                            max_len = 28, round_syms = 32, n_present = 36, pad_sym = 40, len_off = 48,
+                            max_len = 28, round_syms = 32, n_present = 36, pad_sym = 40, table_stride = 44, len_off = 48,
                             lut_off = 56, table_off = 64, sm_off = 72, e_off = 80, blob_size = 88;
 };
 
@@ -41,6 +41,12 @@ template <typename T> inline T load_le(const uint8_t *p) { T v; std::memcpy(&v, 
 inline bool geometry_ok(uint32_t chunk_values, uint32_t stream_values)
 {
     return stream_values != 0 && chunk_values != 0 && stream_values % kTile == 0 && chunk_values % stream_values == 0;
+}
+
+// bytes of one chunk-table entry: the 64-bit offset|mode word and the offsets of the chunk's streams plus its length
+inline uint32_t table_stride_for(uint32_t chunk_values, uint32_t stream_values)
+{
+    return static_cast<uint32_t>(align_up(8 + 4ull * (chunk_values / stream_values + 1), 8));
 }
 
 inline uint32_t round_symbols_for(uint32_t max_len) { return max_len <= 8 ? 4u : 2u; }
@@ -189,7 +195,9 @@ int read_info(const uint8_t *p, size_t size, zm_tensor_info *info, Book *book_ou
     if (chunks != t.n_chunks) return ZM_E_FORMAT;
     if (load_le<uint64_t>(p + Hdr::len_off) != kHeaderBytes || t.lut_offset != kHeaderBytes + 256) return ZM_E_FORMAT;
     if (t.table_offset != align_up(t.lut_offset + (2ull << t.max_len), 16)) return ZM_E_FORMAT;
-    if (t.sm_offset != align_up(t.table_offset + 8ull * (chunks + 1), 256)) return ZM_E_FORMAT;
+    t.table_stride = load_le<uint32_t>(p + Hdr::table_stride);
+    if (t.table_stride != table_stride_for(t.chunk_values, t.stream_values)) return ZM_E_FORMAT;
+    if (t.sm_offset != align_up(t.table_offset + static_cast<uint64_t>(t.table_stride) * (chunks + 1), 256)) return ZM_E_FORMAT;
     if (t.e_offset != align_up(t.sm_offset + t.n_values, 256)) return ZM_E_FORMAT;
     if (t.blob_size < t.e_offset || (t.blob_size & 255)) return ZM_E_FORMAT;
     Book b;
@@ -285,8 +293,9 @@ bool unweave_stream(const uint32_t *words, size_t n_words, uint32_t n, const uin
 
 int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, uint64_t c, uint8_t *e_out)
 {
-    const uint64_t ent = load_le<uint64_t>(p + t.table_offset + 8 * c);
-    const uint64_t nxt = load_le<uint64_t>(p + t.table_offset + 8 * (c + 1));
+    const uint8_t *entry = p + t.table_offset + static_cast<uint64_t>(t.table_stride) * c;
+    const uint64_t ent = load_le<uint64_t>(entry);
+    const uint64_t nxt = load_le<uint64_t>(entry + t.table_stride);
     const uint64_t at = ent & ~15ull, end = nxt & ~15ull, mode = ent & 15;
     if (at < t.e_offset || end < at || end > t.blob_size) return ZM_E_FORMAT;
     const uint64_t first = c * t.chunk_values;
@@ -299,10 +308,9 @@ int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, uint64_t c
     }
     if (mode != ZM_MODE_CODED) return ZM_E_FORMAT;
     const uint32_t streams = (cn + t.stream_values - 1) / t.stream_values;
-    if (end - at < 16 + 4ull * (streams + 1)) return ZM_E_FORMAT;
     const uint8_t *h = p + at;
     for (uint32_t s = 0; s < streams; ++s) {
-        const uint32_t o0 = load_le<uint32_t>(h + 16 + 4 * s), o1 = load_le<uint32_t>(h + 16 + 4 * (s + 1));
+        const uint32_t o0 = load_le<uint32_t>(entry + 8 + 4 * s), o1 = load_le<uint32_t>(entry + 8 + 4 * (s + 1));
         if ((o0 & 3) || o1 < o0 || o1 > end - at) return ZM_E_FORMAT;
         const uint32_t sn = std::min(t.stream_values, cn - s * t.stream_values);
         if (!unweave_stream(reinterpret_cast<const uint32_t *>(h + o0), (o1 - o0) / 4, sn, p + t.lut_offset, t.max_len,
@@ -368,7 +376,8 @@ size_t zm_encode_bound(size_t n_values, uint32_t chunk_values, uint32_t stream_v
     if (!geometry_ok(chunk_values, stream_values)) return 0;
     const size_t chunks = (n_values + chunk_values - 1) / chunk_values;
     // header + code lengths + widest decode table + chunk table + SM section + E-chunks stored raw, each with padding
-    return 384 + (2u << ZM_MAX_CODE_LEN) + 16 + 8 * (chunks + 1) + 256 + (n_values + 256) + (n_values + 16 * chunks) + 256;
+    return 384 + (2u << ZM_MAX_CODE_LEN) + 16 + static_cast<size_t>(table_stride_for(chunk_values, stream_values)) * (chunks + 1) +
+           256 + (n_values + 256) + (n_values + 16 * chunks) + 256;
 }
 
 int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint32_t stream_values,
@@ -382,12 +391,13 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
     if (book.n_present >= 2 && book.kraft != (1u << ZM_MAX_CODE_LEN)) return ZM_E_ARG;   // the decode table must be total
     const size_t chunks = (n_values + chunk_values - 1) / chunk_values;
     if (blob_cap < zm_encode_bound(n_values, chunk_values, stream_values)) return ZM_E_SIZE;
-    if (chunk_offsets && chunk_offsets_cap < chunks + 1) return ZM_E_SIZE;
+    const uint32_t stride = table_stride_for(chunk_values, stream_values);
+    if (chunk_offsets && chunk_offsets_cap < (chunks + 1) * (stride / 8)) return ZM_E_SIZE;
 
     const uint32_t L = book.max_len;
     const uint64_t lut_off = kHeaderBytes + 256;
     const uint64_t table_off = align_up(lut_off + (2ull << L), 16);
-    const uint64_t sm_off = align_up(table_off + 8 * (chunks + 1), 256);
+    const uint64_t sm_off = align_up(table_off + static_cast<uint64_t>(stride) * (chunks + 1), 256);
     const uint64_t e_off = align_up(sm_off + n_values, 256);
     try {
         std::memset(blob, 0, e_off);
@@ -408,38 +418,37 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
         Weaver weaver;
         weaver.prepare(stream_values);
         const uint32_t max_streams = chunk_values / stream_values;
-        std::vector<uint32_t> coded(4 + ((max_streams + 1 + 3) & ~3u) + static_cast<size_t>(max_streams) * stream_word_bound(stream_values));
+        std::vector<uint32_t> coded(static_cast<size_t>(max_streams) * stream_word_bound(stream_values));
         uint64_t pos = e_off;
         for (size_t c = 0; c < chunks; ++c) {
             const size_t first = c * static_cast<size_t>(chunk_values);
             const uint32_t cn = static_cast<uint32_t>(std::min<size_t>(chunk_values, n_values - first));
             const uint32_t streams = (cn + stream_values - 1) / stream_values;
             const uint64_t raw_bytes = align_up(cn, 16);
-            const uint32_t head_words = 4 + ((streams + 1 + 3) & ~3u);
-            std::fill(coded.begin(), coded.begin() + head_words, 0);
-            size_t at = head_words;
+            uint8_t *entry = blob + table_off + static_cast<uint64_t>(stride) * c;      // zero so far
+            size_t at = 0;                                                               // words
             bool smaller = true;
             for (uint32_t s = 0; s < streams; ++s) {
-                coded[4 + s] = static_cast<uint32_t>(4 * at);
+                store_le<uint32_t>(entry + 8 + 4 * s, static_cast<uint32_t>(4 * at));
                 const uint32_t sn = std::min(stream_values, cn - s * stream_values);
                 at += weaver.weave(&expo[first + static_cast<size_t>(s) * stream_values], sn, book, &coded[at]);
                 if (4 * at >= raw_bytes) { smaller = false; break; }
             }
             uint64_t mode;
             if (smaller) {
-                coded[0] = cn; coded[1] = streams; coded[2] = static_cast<uint32_t>(4 * at); coded[3] = 0;
-                coded[4 + streams] = static_cast<uint32_t>(4 * at);
+                store_le<uint32_t>(entry + 8 + 4 * streams, static_cast<uint32_t>(4 * at));
                 std::memcpy(blob + pos, coded.data(), 4 * at);
                 mode = ZM_MODE_CODED;
             } else {
+                std::memset(entry, 0, stride);
                 std::memset(blob + pos, 0, raw_bytes);
                 std::memcpy(blob + pos, &expo[first], cn);
                 mode = ZM_MODE_RAW;
             }
-            store_le<uint64_t>(blob + table_off + 8 * c, pos | mode);
+            store_le<uint64_t>(entry, pos | mode);
             pos += smaller ? 4 * at : raw_bytes;
         }
-        store_le<uint64_t>(blob + table_off + 8 * chunks, pos);
+        store_le<uint64_t>(blob + table_off + static_cast<uint64_t>(stride) * chunks, pos);
         const uint64_t total = align_up(pos, 256);
         std::memset(blob + pos, 0, total - pos);
 
@@ -453,6 +462,7 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
         store_le<uint32_t>(blob + Hdr::round_syms, round_symbols_for(L));
         store_le<uint32_t>(blob + Hdr::n_present, book.n_present);
         store_le<uint32_t>(blob + Hdr::pad_sym, book.pad);
+        store_le<uint32_t>(blob + Hdr::table_stride, stride);
         store_le<uint64_t>(blob + Hdr::len_off, kHeaderBytes);
         store_le<uint64_t>(blob + Hdr::lut_off, lut_off);
         store_le<uint64_t>(blob + Hdr::table_off, table_off);
@@ -461,7 +471,7 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
         store_le<uint64_t>(blob + Hdr::blob_size, total);
         *blob_size = total;
         if (n_chunks) *n_chunks = chunks;
-        if (chunk_offsets) std::memcpy(chunk_offsets, blob + table_off, 8 * (chunks + 1));
+        if (chunk_offsets) std::memcpy(chunk_offsets, blob + table_off, static_cast<size_t>(stride) * (chunks + 1));
     } catch (const std::bad_alloc &) { return ZM_E_NOMEM; }
     return ZM_OK;
 }
@@ -481,7 +491,6 @@ int zm_validate_blob(const void *blob_host, size_t size)
     if (rc != ZM_OK) return rc;
     if (t.blob_size > size) return ZM_E_FORMAT;
     for (size_t i = Hdr::blob_size + 8; i < kHeaderBytes; ++i) if (p[i]) return ZM_E_FORMAT;
-    if (load_le<uint32_t>(p + 44)) return ZM_E_FORMAT;
     // decode table must be the one the code lengths define
     std::vector<uint8_t> lut(2u << t.max_len);
     fill_decode_table(book, lut.data());
@@ -490,31 +499,33 @@ int zm_validate_blob(const void *blob_host, size_t size)
     uint64_t expect = t.e_offset;
     const uint64_t word_cap = stream_word_bound(t.stream_values);
     for (uint64_t c = 0; c < t.n_chunks; ++c) {
-        const uint64_t ent = load_le<uint64_t>(p + t.table_offset + 8 * c);
-        const uint64_t nxt = load_le<uint64_t>(p + t.table_offset + 8 * (c + 1));
+        const uint8_t *entry = p + t.table_offset + static_cast<uint64_t>(t.table_stride) * c;
+        const uint64_t ent = load_le<uint64_t>(entry);
+        const uint64_t nxt = load_le<uint64_t>(entry + t.table_stride);
         const uint64_t at = ent & ~15ull, end = nxt & ~15ull, mode = ent & 15;
         if (at != expect || end < at || end > t.blob_size) return ZM_E_FORMAT;
         const uint64_t cn = std::min<uint64_t>(t.chunk_values, t.n_values - c * t.chunk_values);
+        uint64_t used_slots = 0;                     // 32-bit offset slots of the entry that carry data
         if (mode == ZM_MODE_RAW) {
             if (end - at != align_up(cn, 16)) return ZM_E_FORMAT;
         } else if (mode == ZM_MODE_CODED) {
             const uint64_t streams = (cn + t.stream_values - 1) / t.stream_values;
-            const uint64_t head = 16 + align_up(4 * (streams + 1), 16);
-            if (end - at < head) return ZM_E_FORMAT;
-            const uint8_t *h = p + at;
-            if (load_le<uint32_t>(h) != cn || load_le<uint32_t>(h + 4) != streams || load_le<uint32_t>(h + 8) != end - at || load_le<uint32_t>(h + 12)) return ZM_E_FORMAT;
-            if (load_le<uint32_t>(h + 16) != head || load_le<uint32_t>(h + 16 + 4 * streams) != end - at) return ZM_E_FORMAT;
+            used_slots = streams + 1;
+            if (load_le<uint32_t>(entry + 8) != 0 || load_le<uint32_t>(entry + 8 + 4 * streams) != end - at) return ZM_E_FORMAT;
             for (uint64_t s = 0; s < streams; ++s) {
-                const uint32_t o0 = load_le<uint32_t>(h + 16 + 4 * s), o1 = load_le<uint32_t>(h + 16 + 4 * (s + 1));
+                const uint32_t o0 = load_le<uint32_t>(entry + 8 + 4 * s), o1 = load_le<uint32_t>(entry + 8 + 4 * (s + 1));
                 if ((o0 & 15) || (o1 & 15) || o1 < o0 || o1 > end - at) return ZM_E_FORMAT;
                 const uint64_t words = (o1 - o0) / 4;
                 if (words < 2 * kLanes || words > word_cap) return ZM_E_FORMAT;
             }
         } else return ZM_E_FORMAT;
+        for (uint64_t j = 8 + 4 * used_slots; j < t.table_stride; j += 4) if (load_le<uint32_t>(entry + j)) return ZM_E_FORMAT;
         expect = end;
     }
-    const uint64_t last = load_le<uint64_t>(p + t.table_offset + 8ull * t.n_chunks);
+    const uint8_t *last_entry = p + t.table_offset + static_cast<uint64_t>(t.table_stride) * t.n_chunks;
+    const uint64_t last = load_le<uint64_t>(last_entry);
     if (last != expect || align_up(last, 256) != t.blob_size) return ZM_E_FORMAT;
+    for (uint64_t j = 8; j < t.table_stride; j += 4) if (load_le<uint32_t>(last_entry + j)) return ZM_E_FORMAT;
     return ZM_OK;
 }
 

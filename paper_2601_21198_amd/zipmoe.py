@@ -33,7 +33,8 @@ class TensorInfo(ctypes.Structure):
     _fields_ = [("n_values", ctypes.c_uint64), ("blob_size", ctypes.c_uint64), ("lut_offset", ctypes.c_uint64),
                 ("table_offset", ctypes.c_uint64), ("sm_offset", ctypes.c_uint64), ("e_offset", ctypes.c_uint64),
                 ("chunk_values", ctypes.c_uint32), ("stream_values", ctypes.c_uint32), ("n_chunks", ctypes.c_uint32),
-                ("max_len", ctypes.c_uint32), ("round_symbols", ctypes.c_uint32), ("n_present", ctypes.c_uint32)]
+                ("max_len", ctypes.c_uint32), ("round_symbols", ctypes.c_uint32), ("n_present", ctypes.c_uint32),
+                ("table_stride", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 class TensorParts(ctypes.Structure):
@@ -160,7 +161,8 @@ def encode_bound(n_values: int, chunk_values: int, stream_values: int) -> int:
 
 
 def encode(bf16, chunk_values: int, stream_values: int, code_len) -> Tuple[np.ndarray, np.ndarray]:
-    """zm_encode: returns (blob as uint8 array, chunk_offsets as uint64 array of n_chunks+1 entries)."""
+    """zm_encode: returns (blob as uint8 array, chunk table as uint64 array shaped [n_chunks+1, table_stride/8]:
+    column 0 is the offset|mode word of every chunk, the last row holds the end offset)."""
     w = _words(bf16)
     cl = np.ascontiguousarray(code_len, np.uint8)
     cap = encode_bound(w.size, chunk_values, stream_values)
@@ -168,12 +170,13 @@ def encode(bf16, chunk_values: int, stream_values: int, code_len) -> Tuple[np.nd
         raise ZipMoEError(E_ARG, "zm_encode_bound")
     blob = np.empty(cap, np.uint8)
     max_chunks = -(-w.size // chunk_values) + 1
-    offs = np.zeros(max_chunks, np.uint64)
+    words_per_entry = -(-(8 + 4 * (chunk_values // stream_values + 1)) // 8)
+    offs = np.zeros(max_chunks * words_per_entry, np.uint64)
     size, n_chunks = ctypes.c_size_t(0), ctypes.c_size_t(0)
     _check(lib().zm_encode(_ptr(w, ctypes.c_uint16), w.size, chunk_values, stream_values, _ptr(cl, ctypes.c_uint8),
                            _ptr(blob, ctypes.c_uint8), cap, ctypes.byref(size),
                            _ptr(offs, ctypes.c_uint64), offs.size, ctypes.byref(n_chunks)), "zm_encode")
-    return blob[: size.value].copy(), offs[: n_chunks.value + 1].copy()
+    return blob[: size.value].copy(), offs[: (n_chunks.value + 1) * words_per_entry].reshape(-1, words_per_entry).copy()
 
 
 def compress(bf16, chunk_values: int, stream_values: int = 4096, max_len: int = 8) -> Tuple[np.ndarray, np.ndarray]:

@@ -174,7 +174,7 @@ def test_decode_tensors_with_parts_in_separate_allocations():
         info = zm.blob_info(b)
         infos[i] = info
         cut = lambda lo, hi: torch.from_numpy(b[lo:hi].copy()).cuda()
-        pieces = [cut(info.lut_offset, info.table_offset), cut(info.table_offset, info.table_offset + 8 * (info.n_chunks + 1)),
+        pieces = [cut(info.lut_offset, info.table_offset), cut(info.table_offset, info.table_offset + info.table_stride * (info.n_chunks + 1)),
                   cut(info.sm_offset, info.e_offset), cut(info.e_offset, info.blob_size)]
         out = torch.full((int(info.n_values) + 2 * GUARD,), GUARD_WORD, dtype=torch.int16, device="cuda")
         keep.append((pieces, out))

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(zm.TensorInfo) == 72
+    assert ctypes.sizeof(zm.TensorInfo) == 80
 
 
 @pytest.mark.parametrize("kind,max_len", [("gauss", 8), ("gauss", 12), ("wide", 8), ("wide", 12), ("rare_last", 8),
@@ -75,8 +75,8 @@ def test_blobs_identical_to_reference_and_decodable(kind, n):
                 info.round_symbols, info.n_present) == (n, C, W, h["n_chunks"], h["L"], h["R"], h["n_present"])
         assert (info.lut_offset, info.table_offset, info.sm_offset, info.e_offset, info.blob_size) == \
                (h["lut_offset"], h["table_offset"], h["sm_offset"], h["e_offset"], h["blob_size"])
-        table = blob[h["table_offset"]: h["table_offset"] + 8 * (h["n_chunks"] + 1)].view("<u8")
-        assert np.array_equal(offs, table)
+        table = blob[h["table_offset"]: h["table_offset"] + h["table_stride"] * (h["n_chunks"] + 1)].view("<u8")
+        assert info.table_stride == h["table_stride"] and np.array_equal(offs.reshape(-1), table)
 
 
 def test_workload_tensors_match_reference():
@@ -111,7 +111,7 @@ def test_validate_rejects_damage():
     info = zm.blob_info(blob)
     for off in (0, 4, 8, 16, 20, 24, 28, 32, 36, 40, 44, 56, 64, 72, 80, 88, 100,
                 128 + int(np.argmax(blob[128:384])), info.lut_offset + 3, info.table_offset, info.table_offset + 9,
-                int(offs[0]) & ~15, (int(offs[0]) & ~15) + 4, (int(offs[0]) & ~15) + 17, (int(offs[1]) & ~15) + 8):
+                info.table_offset + 12, info.table_offset + info.table_stride + 16, info.table_offset + info.table_stride - 1):
         bad = blob.copy()
         bad[off] ^= 0x11
         with pytest.raises(zm.ZipMoEError):
