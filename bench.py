@@ -30,8 +30,8 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published peak HBM3E bandwidth
 # copy of known size; the summaries are under profiles/).  Valid only for the kernel source they were taken
 # with: the entry is reported only while the source's hash still matches, else "traffic" is null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256_16": "34499c14aad8e59b",
-    "bytes_per_launch": {"cfg5": 118.87e6, "cfg4": 1214.50e6},
+    "kernel_sha256_16": "75e9df5f03a5291f",
+    "bytes_per_launch": {"cfg5": 118.56e6, "cfg4": 1211.28e6},
 }
 
 
