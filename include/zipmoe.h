@@ -21,8 +21,9 @@
  * Conventions
  *   - Every function returns an int status: ZM_OK or a negative ZM_E_* code,
  *     unless stated otherwise.  No function throws, none keeps global state,
- *     none keeps a pointer it was given.  Functions are thread-safe as long as
- *     concurrent calls write distinct outputs.
+ *     and none but the zm_cache object (which says so) keeps a pointer it was
+ *     given.  Functions are thread-safe as long as concurrent calls write
+ *     distinct outputs.
  *   - "host" pointers are ordinary process memory; "device" pointers are HIP
  *     device memory of the current device.  The caller owns every buffer.
  *   - bf16 values are passed as their 16-bit patterns (uint16_t), row-major.
