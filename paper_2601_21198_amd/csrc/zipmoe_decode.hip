@@ -82,12 +82,18 @@ __device__ __forceinline__ void recover4(uint32_t e4, uint32_t sm4, uint32_t &w0
     w23 = __builtin_amdgcn_perm(hi4, lo4, 0x07030602u);
 }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// kStreaming: the output of the launch is larger than the last-level cache, so the stores are marked
+// non-temporal; smaller outputs are written normally and tend to stay cached for their consumer.
+template <bool kStreaming = false>
 __device__ __forceinline__ void recover_and_store(uint16_t *dst, uint2 e, uint2 sm)
 {
     uint4 w;
     recover4(e.x, sm.x, w.x, w.y);
     recover4(e.y, sm.y, w.z, w.w);
-    *reinterpret_cast<uint4 *>(dst) = w;
+    if constexpr (kStreaming) __builtin_nontemporal_store((u32x4){w.x, w.y, w.z, w.w}, reinterpret_cast<u32x4 *>(dst));
+    else *reinterpret_cast<uint4 *>(dst) = w;
 }
 
 // Same for a lane that owns fewer than eight values of the tile.
@@ -158,8 +164,8 @@ struct Decoder {
     }
 };
 
-// R: symbols per round; kWaves: waves (streams) per workgroup
-template <int R, int kWaves>
+// R: symbols per round; kWaves: waves (streams) per workgroup; kStreaming: non-temporal stores
+template <int R, int kWaves, bool kStreaming>
 __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
 {
     // Byte tables of the workgroup's tensor, at fixed LDS addresses so that a lookup is one LDS read with
@@ -295,7 +301,7 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     if (mode == ZM_MODE_CODED && full) {
 #pragma unroll
         for (int k = 0; k < kGroup; ++k)
-            recover_and_store(out_base + k * kTile, dec.tile(len_tab, sym_tab), sm[k]);
+            recover_and_store<kStreaming>(out_base + k * kTile, dec.tile(len_tab, sym_tab), sm[k]);
         return;
     }
 
@@ -317,7 +323,7 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
                 uint2 ev = make_uint2(0u, 0u);
                 if (mode == ZM_MODE_CODED) ev = dec.tile(len_tab, sym_tab);
                 else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
-                if (left >= 8) recover_and_store(out_base + tile * kTile, ev, sm[k]);
+                if (left >= 8) recover_and_store<kStreaming>(out_base + tile * kTile, ev, sm[k]);
                 else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, sm[k], left);
             }
         }
@@ -368,6 +374,7 @@ inline size_t stream_cap_words(uint32_t stream_values, uint32_t max_len_bound)
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;
+constexpr uint64_t kLastLevelCacheBytes = 256ull << 20;   // MI355X Infinity Cache
 
 template <int R, int kWaves>
 int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
@@ -383,7 +390,12 @@ int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
         blocks = b > blocks ? b : blocks;
     }
     if (!blocks) return ZM_OK;
-    hipLaunchKernelGGL((zm_decode_kernel<R, kWaves>), dim3(blocks, L.n_tasks), dim3(64 * kWaves), lds, stream, L);
+    uint64_t out_bytes = 0;
+    for (uint32_t k = 0; k < L.n_tasks; ++k) out_bytes += 2 * L.task[k].n_values;
+    if (out_bytes > kLastLevelCacheBytes)
+        hipLaunchKernelGGL((zm_decode_kernel<R, kWaves, true>), dim3(blocks, L.n_tasks), dim3(64 * kWaves), lds, stream, L);
+    else
+        hipLaunchKernelGGL((zm_decode_kernel<R, kWaves, false>), dim3(blocks, L.n_tasks), dim3(64 * kWaves), lds, stream, L);
     return hipGetLastError() == hipSuccess ? ZM_OK : ZM_E_HIP;
 }
 
