@@ -12,7 +12,6 @@ decoder timed on the host cores on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
-import ctypes
 import json
 import os
 import sys
@@ -51,7 +50,7 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def build_layer(wl, layer: int, stream_values: int, max_len: int, workers: int, keep_blobs_of=None):
+def build_layer(wl, layer: int, stream_values: int, max_len: int, workers: int):
     """Generates and compresses every expert of one layer; returns (blobs per expert, algorithmic bytes per expert)."""
     from paper_2601_21198_amd import synth, zipmoe as zm
 

@@ -163,3 +163,52 @@ def test_host_exponent_decoder_on_workload_tensor():
     w = synth.expert_matrix(synth.CFG2, 0, 0, 1)
     blob, _ = zm.compress(w, 16384, 4096)
     assert np.array_equal(zm.decode_exponents_host(blob, n_threads=4), zo.split(w)[0])
+
+
+def test_decode_entry_points_refuse_bad_arguments_before_any_launch():
+    """argument checks of the device entry points are host logic: they return before touching the GPU"""
+    w = synth.special_tensor("gauss", 5000, 0)
+    blob, _ = zm.compress(w, 4096, 4096)
+    info = zm.blob_info(blob)
+    infos = (zm.TensorInfo * 1)(info)
+    P = ctypes.POINTER(ctypes.c_void_p)
+    good = 0x10000                                             # an aligned, non-null address; never dereferenced
+    outs = (ctypes.c_void_p * 1)(good)
+    L = zm.lib()
+    parts = (zm.TensorParts * 1)(zm.TensorParts(good, good, good, good))
+    assert L.zm_decode_tensors(parts, infos, 0, outs, None) == zm.OK           # nothing to do
+    assert L.zm_decode_tensors(None, infos, 1, outs, None) == zm.E_ARG
+    assert L.zm_decode_tensors(parts, infos, 257, outs, None) == zm.E_ARG
+    for bad in (zm.TensorParts(good + 4, good, good, good), zm.TensorParts(good, good + 1, good, good),
+                zm.TensorParts(good, good, good + 8, good), zm.TensorParts(good, good, good, None)):
+        assert L.zm_decode_tensors((zm.TensorParts * 1)(bad), infos, 1, outs, None) == zm.E_ARG
+    assert L.zm_decode_tensors(parts, infos, 1, (ctypes.c_void_p * 1)(good + 2), None) == zm.E_ARG
+    broken = zm.TensorInfo.from_buffer_copy(info)
+    broken.stream_values = 1000
+    assert L.zm_decode_tensors(parts, (zm.TensorInfo * 1)(broken), 1, outs, None) == zm.E_ARG
+    broken = zm.TensorInfo.from_buffer_copy(info)
+    broken.table_stride = 8
+    assert L.zm_decode_tensors(parts, (zm.TensorInfo * 1)(broken), 1, outs, None) == zm.E_ARG
+    blobs = (ctypes.c_void_p * 1)(good)
+    ids = (ctypes.c_int32 * 1)(0)
+    assert L.zm_decode_experts(blobs, blobs, infos, 1, 1, ids, 0, outs, None) == zm.OK
+    assert L.zm_decode_experts(blobs, blobs, infos, 1, 1, (ctypes.c_int32 * 1)(1), 1, outs, None) == zm.E_ARG
+    assert L.zm_decode_experts(blobs, blobs, infos, 0, 1, ids, 1, outs, None) == zm.E_ARG
+    assert L.zm_decode_experts((ctypes.c_void_p * 1)(good + 8), blobs, infos, 1, 1, ids, 1, outs, None) == zm.E_ARG
+    assert L.zm_recover(None, ctypes.c_void_p(good), 8, ctypes.c_void_p(good), None) == zm.E_ARG
+    assert L.zm_recover(ctypes.c_void_p(good), ctypes.c_void_p(good), 0, ctypes.c_void_p(good), None) == zm.OK
+
+
+def test_cache_configuration_is_checked_on_the_host():
+    w = synth.special_tensor("gauss", 5000, 0)
+    blob, _ = zm.compress(w, 4096, 4096)
+    infos = (zm.TensorInfo * 2)(zm.blob_info(blob), zm.blob_info(blob))
+    need = ctypes.c_size_t(0)
+    ok = zm.CacheConfig(2, 1, (ctypes.c_int32 * 4)(1, 1, 0, 0), 0, 2)
+    assert zm.lib().zm_cache_arena_bytes(ctypes.byref(ok), infos, ctypes.byref(need)) == zm.OK
+    info = infos[0]
+    sm, e, full = -(-(info.e_offset - info.sm_offset) // 256) * 256, -(-(info.blob_size - info.e_offset) // 256) * 256, -(-2 * 5000 // 256) * 256
+    assert need.value >= full + (sm + e) + 2 * (sm + e + full)             # pools F and C plus two transient buffers
+    for bad in (zm.CacheConfig(0, 1, (ctypes.c_int32 * 4)(1, 1, 0, 0), 0, 2), zm.CacheConfig(2, 1, (ctypes.c_int32 * 4)(-1, 1, 0, 0), 0, 2),
+                zm.CacheConfig(2, 1, (ctypes.c_int32 * 4)(1, 1, 0, 0), -1, 2), zm.CacheConfig(2, 1, (ctypes.c_int32 * 4)(1, 1, 0, 0), 0, 300)):
+        assert zm.lib().zm_cache_arena_bytes(ctypes.byref(bad), infos, ctypes.byref(need)) == zm.E_ARG
