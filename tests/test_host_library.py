@@ -212,3 +212,18 @@ def test_cache_configuration_is_checked_on_the_host():
     for bad in (zm.CacheConfig(0, 1, (ctypes.c_int32 * 4)(1, 1, 0, 0), 0, 2), zm.CacheConfig(2, 1, (ctypes.c_int32 * 4)(-1, 1, 0, 0), 0, 2),
                 zm.CacheConfig(2, 1, (ctypes.c_int32 * 4)(1, 1, 0, 0), -1, 2), zm.CacheConfig(2, 1, (ctypes.c_int32 * 4)(1, 1, 0, 0), 0, 300)):
         assert zm.lib().zm_cache_arena_bytes(ctypes.byref(bad), infos, ctypes.byref(need)) == zm.E_ARG
+
+
+def test_serialised_format_is_stable():
+    """the stored digests were written by the reference codec alone (tests/golden/make_format_digests.py);
+    the reference codec of today and the library must both still produce those bytes"""
+    import hashlib
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "format_digests.txt")) if not l.startswith("#")]
+    assert len(rows) == 6
+    for kind, n, C, W, max_len, version, size, digest in rows:
+        w = synth.special_tensor(kind, int(n), seed=1)
+        ref, lengths = zo.encode_tensor(w, int(C), int(W), int(max_len))
+        assert zo.header(ref)["version"] == int(version) and ref.size == int(size)
+        assert hashlib.sha256(ref.tobytes()).hexdigest() == digest
+        mine, _ = zm.encode(w, int(C), int(W), lengths)
+        assert hashlib.sha256(mine.tobytes()).hexdigest() == digest
