@@ -186,3 +186,26 @@ def test_decode_tensors_with_parts_in_separate_allocations():
         a = out.cpu().numpy().view(np.uint16)
         assert np.all(a[:GUARD] == GUARD_WORD) and np.all(a[-GUARD:] == GUARD_WORD)
         assert np.array_equal(a[GUARD:-GUARD], zo.decode(b)) and np.array_equal(a[GUARD:-GUARD], w)
+
+
+def test_limits_of_one_call():
+    """256 tensors in one call is the most a call takes (six launches); one more is refused; a stream too long to
+    stage in LDS is refused on the host; the longest stream one wave can stage decodes correctly"""
+    import torch
+    small = [synth.special_tensor("gauss", 600 + i, seed=i) for i in range(256)]
+    blobs = [zm.compress(w, 1024, 512)[0] for w in small]
+    got = gpu_decode_tensors(blobs)
+    for w, g in zip(small, got):
+        assert np.array_equal(g, w)
+    with pytest.raises(zm.ZipMoEError):
+        gpu_decode_tensors(blobs + blobs[:1])
+    # streams of 32768 values: only one fits the LDS of a workgroup
+    w = synth.special_tensor("gauss", 2 * 32768 + 999, seed=3)
+    blob, _ = zm.compress(w, 32768, 32768)
+    assert np.array_equal(gpu_decode_tensors([blob])[0], w) and np.array_equal(zo.decode(blob), w)
+    # streams of 131072 values can not be staged: refused, nothing launched
+    big, _ = zm.compress(synth.special_tensor("gauss", 131072, seed=4), 131072, 131072)
+    with pytest.raises(zm.ZipMoEError):
+        gpu_decode_tensors([big])
+    assert np.array_equal(zo.decode(big), synth.special_tensor("gauss", 131072, seed=4))
+    torch.cuda.synchronize()
