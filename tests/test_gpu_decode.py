@@ -209,3 +209,35 @@ def test_limits_of_one_call():
         gpu_decode_tensors([big])
     assert np.array_equal(zo.decode(big), synth.special_tensor("gauss", 131072, seed=4))
     torch.cuda.synchronize()
+
+
+def test_decode_call_can_be_captured_in_a_hip_graph():
+    """the hot call allocates nothing and copies nothing, so it can be recorded into a graph; every replay,
+    with eager work and synchronisations in between, must give the eager result"""
+    import torch
+    wl = synth.CFG2
+    tensors = synth.expert_tensors(wl, 0, 0)
+    blobs = compress_expert(wl, 0, 0)
+    layer = zm.ExpertLayer([blobs, blobs])
+    bufs, starts, vals = layer.alloc_outputs(2)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    call = layer.make_call([1, 0], bufs, starts)
+    with torch.cuda.stream(side):
+        call(side.cuda_stream)                                  # eager warm-up on the capture stream
+    side.synchronize()
+    eager = [b.clone() for b in bufs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(torch.cuda.current_stream().cuda_stream)
+    for replay in range(4):
+        for b in bufs:
+            b.fill_(0x2222 + replay)                            # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for b, e in zip(bufs, eager):
+            assert torch.equal(b, e), replay
+    got = bufs[0].cpu().numpy().view(np.uint16)
+    for m in range(3):
+        assert np.array_equal(got[starts[m]: starts[m] + vals[m]], tensors[m].reshape(-1))
