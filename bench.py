@@ -153,6 +153,39 @@ def bench_split(args, wl, workers: int, steps: int, warmup: int) -> int:
     return 0
 
 
+def bench_cache(args, wl, workers: int, steps: int, warmup: int) -> int:
+    """zm_cache_fetch over the workload's routing on its first layer: host blobs pinned, pools as given."""
+    import torch
+    from paper_2601_21198_amd import synth, zipmoe as zm
+
+    slots = [int(x) for x in args.slots.split(",")]
+    blobs, _, n_values = build_layer(wl, 0, args.stream_values, args.max_len, workers)
+    cache = zm.ExpertCache(blobs, slots, args.tolerance, max_selected=wl.top_k)
+    stream = torch.cuda.current_stream().cuda_stream
+    routes = [synth.route(wl, 0, s) for s in range(warmup + steps)]
+    for r in routes[:warmup]:
+        cache.fetch(r, stream)
+    torch.cuda.synchronize()
+    found = [0] * 5
+    t0 = time.perf_counter()
+    for r in routes[warmup:]:
+        for f in cache.fetch(r, stream)[1]:
+            found[f] += 1
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    out_bytes = sum(2.0 * n_values[int(e)] for r in routes[warmup:] for e in r)
+    print(json.dumps({
+        "metric": "bf16 GB/s made available by zm_cache_fetch (pools in HBM, host memory below)",
+        "value": round(out_bytes / wall / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(wall * 1e3 / steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": wl.name, "path": "cache", "slots_F_C_S_E": slots, "tolerance": args.tolerance,
+                   "arena_bytes": int(cache.arena.numel()), "found_in_F_C_S_E_none": found},
+    }), flush=True)
+    cache.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,9 +196,12 @@ def main() -> int:
     ap.add_argument("--max-len", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verify", action="store_true", help="compare the last step's output with the originals")
-    ap.add_argument("--path", default="fused", choices=["fused", "split"],
+    ap.add_argument("--path", default="fused", choices=["fused", "split", "cache"],
                     help="fused: zm_decode_experts (default, the line the driver reads); split: the paper's own "
-                         "division of work -- zm_decode_exponents_host on host threads, zm_recover on the GPU")
+                         "division of work -- zm_decode_exponents_host on host threads, zm_recover on the GPU; "
+                         "cache: zm_cache_fetch on the workload's first layer under --slots")
+    ap.add_argument("--slots", default="8,16,16,16", help="--path cache: capacities of the pools F,C,S,E in experts")
+    ap.add_argument("--tolerance", type=int, default=1, help="--path cache: the rank tolerance delta")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="before the timed region, run a plain device copy of this many MiB three times "
                          "(a kernel of known traffic that scales the profiler's HBM byte counters)")
@@ -188,6 +224,9 @@ def main() -> int:
     steps = args.steps if args.steps is not None else default_steps[0]
     warmup = args.warmup if args.warmup is not None else default_steps[1]
 
+    if args.path == "cache":
+        return bench_cache(args, wl, workers, args.steps if args.steps is not None else 200,
+                           args.warmup if args.warmup is not None else 200)
     if args.path == "split":
         return bench_split(args, wl, workers, steps if args.steps is not None else 200, warmup if args.warmup is not None else 20)
 
