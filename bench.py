@@ -153,6 +153,48 @@ def bench_split(args, wl, workers: int, steps: int, warmup: int) -> int:
     return 0
 
 
+def plan_from_measurements(wl, blobs, routes, memory_bytes: float):
+    """Inputs of zm_plan_pools taken from this run: the rank-based inclusion list from the routing draws, the
+    per-expert size of each pool's form from the blobs, and the three delays of the makespan estimate from a
+    timed host-to-device copy of one expert's SM sections and E-chunk regions and one timed decode."""
+    import torch
+    from paper_2601_21198_amd import zipmoe as zm
+
+    counts = np.zeros(wl.n_experts)
+    for r in routes:
+        counts[r] += 1
+    f = np.sort(counts)[::-1] / len(routes)                      # rank 0 first; sums to top_k
+    infos = [zm.blob_info(b[:384]) for b in blobs[0]]
+    sm_b = sum(int(i.e_offset - i.sm_offset) for i in infos)
+    e_b = sum(int(i.blob_size - i.e_offset) for i in infos)
+    full_b = sum(2 * int(i.n_values) for i in infos)
+    shards = max(int(i.n_chunks) for i in infos)
+
+    def timed(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    pin_sm = torch.empty(sm_b, dtype=torch.uint8, pin_memory=True)
+    pin_e = torch.empty(e_b, dtype=torch.uint8, pin_memory=True)
+    dev = torch.empty(max(sm_b, e_b), dtype=torch.uint8, device="cuda")
+    t_sm = timed(lambda: dev[:sm_b].copy_(pin_sm, non_blocking=True))
+    t_e = timed(lambda: dev[:e_b].copy_(pin_e, non_blocking=True))
+    layer = zm.ExpertLayer([blobs[0]], validate=False)
+    bufs, starts, _ = layer.alloc_outputs(1)
+    call = layer.make_call([0], bufs, starts)
+    t_dec = timed(lambda: call(torch.cuda.current_stream().cuda_stream))
+    n_t = len(infos)
+    costs = zm.PlanCosts(t_dec / (n_t * shards), t_e / (n_t * shards), t_sm / n_t, 1, shards, n_t)
+    ratios, slots, cost = zm.plan_pools(f, wl.top_k, costs, memory_bytes, (full_b, sm_b + e_b, sm_b, e_b), 10)
+    return {"memory_bytes": memory_bytes, "ratios": ratios, "slots": slots, "expected_makespan_s": cost,
+            "sm_copy_s_per_expert": t_sm, "e_copy_s_per_expert": t_e, "decode_s_per_expert": t_dec}
+
+
 def bench_cache(args, wl, workers: int, steps: int, warmup: int) -> int:
     """zm_cache_fetch over the workload's routing on its first layer: host blobs pinned, pools as given."""
     import torch
@@ -160,9 +202,13 @@ def bench_cache(args, wl, workers: int, steps: int, warmup: int) -> int:
 
     slots = [int(x) for x in args.slots.split(",")]
     blobs, _, n_values = build_layer(wl, 0, args.stream_values, args.max_len, workers)
+    routes = [synth.route(wl, 0, s) for s in range((args.warmup or 200) + (args.steps or 200))]
+    plan = None
+    if args.plan_memory_gb is not None:
+        plan = plan_from_measurements(wl, blobs, routes, args.plan_memory_gb * 1e9)
+        slots = plan["slots"]
     cache = zm.ExpertCache(blobs, slots, args.tolerance, max_selected=wl.top_k)
     stream = torch.cuda.current_stream().cuda_stream
-    routes = [synth.route(wl, 0, s) for s in range(warmup + steps)]
     for r in routes[:warmup]:
         cache.fetch(r, stream)
     torch.cuda.synchronize()
@@ -180,7 +226,7 @@ def bench_cache(args, wl, workers: int, steps: int, warmup: int) -> int:
         "ms_per_step": round(wall * 1e3 / steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": wl.name, "path": "cache", "slots_F_C_S_E": slots, "tolerance": args.tolerance,
-                   "arena_bytes": int(cache.arena.numel()), "found_in_F_C_S_E_none": found},
+                   "arena_bytes": int(cache.arena.numel()), "found_in_F_C_S_E_none": found, "plan": plan},
     }), flush=True)
     cache.close()
     return 0
@@ -202,6 +248,9 @@ def main() -> int:
                          "cache: zm_cache_fetch on the workload's first layer under --slots")
     ap.add_argument("--slots", default="8,16,16,16", help="--path cache: capacities of the pools F,C,S,E in experts")
     ap.add_argument("--tolerance", type=int, default=1, help="--path cache: the rank tolerance delta")
+    ap.add_argument("--plan-memory-gb", type=float, default=None,
+                    help="--path cache: instead of --slots, let zm_plan_pools split this much HBM over the pools, "
+                         "from the routing's rank-based inclusion frequencies and delays measured in the run")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="before the timed region, run a plain device copy of this many MiB three times "
                          "(a kernel of known traffic that scales the profiler's HBM byte counters)")
