@@ -354,6 +354,94 @@ int zm_decode_exponents_host(const void *blob_host, size_t size, uint32_t chunk_
  * pointers, ZM_E_HIP if the launch fails. */
 int zm_recover(const void *exponents, const void *sign_mantissa, size_t n_values, void *out_bf16, void *stream);
 
+/* ---- Cache-affinity scheduling of one sparse layer's reconstruction tasks
+ * (Sec. 3.3 "Cache-Affinity Scheduler", App. A; analysis in App. B).  Host only,
+ * double precision.  The machine model is the paper's: one I/O thread, L
+ * decompression threads, one GPU stream.  A task is one tensor of one selected
+ * expert; it reads K E-chunks (each `e_read`) and/or one SM-chunk (`sm_read`)
+ * if they are not in memory, decompresses K E-chunks (each `decompress`, one
+ * thread each, ready when that E-chunk has arrived), is recovered on the GPU
+ * stream (`recover`) when all of that is done, and the expert runs for
+ * expert_time[expert] on the GPU stream once all its tensors are recovered.
+ * The makespan is the end of the last execution. ---- */
+
+typedef struct zm_sched_task {
+    int32_t expert;        /* n(j): index into expert_time */
+    int32_t needs_sm;      /* the SM-chunk must be read: the task is Type-I */
+    int32_t needs_e;       /* the E-chunks must be read */
+    int32_t needs_decode;  /* 0: the tensor is held in full, no operation but the execution */
+} zm_sched_task;
+
+typedef struct zm_sched_costs {
+    double sm_read;        /* u */
+    double e_read;         /* rho * u / K */
+    double decompress;     /* c */
+    double recover;        /* per tensor on the GPU stream; 0 gives the paper's model */
+    int32_t threads;       /* L >= 1 */
+    int32_t shards;        /* K >= 1 */
+} zm_sched_costs;
+
+#define ZM_OP_E_READ 0
+#define ZM_OP_SM_READ 1
+#define ZM_OP_DECOMPRESS 2
+#define ZM_OP_RECOVER 3
+#define ZM_OP_EXECUTE 4
+
+typedef struct zm_sched_event {
+    int32_t kind;          /* ZM_OP_* */
+    int32_t task;          /* task index; the expert index for ZM_OP_EXECUTE */
+    int32_t chunk;         /* E-chunk index for reads of E-chunks and decompressions, else 0 */
+    int32_t unit;          /* decompression thread for ZM_OP_DECOMPRESS, else 0 */
+    double start;
+    double end;
+} zm_sched_event;
+
+typedef struct zm_sched_result {
+    double makespan;       /* end of the last operation on the GPU stream */
+    double io_end;         /* end of the last read */
+    double charge;         /* App. B: total idle time in front of decompressions on their threads */
+} zm_sched_result;
+
+/* App. A, Alg. 1: builds the blocks.  Type-I and Type-II tasks are each sorted
+ * by non-increasing expert_time (ties: expert index, then task index).  A block
+ * starts with the first Type-I task left; until it is compute-dominant (the l-th
+ * earliest decompression thread ends at least l * e_read after the I/O thread,
+ * l = 1..min(L, K)) the next task of (Type-II, then Type-I) goes to the earliest
+ * position that does not increase the total charge, else behind the last task of
+ * the block of the preferred class (Type-II if the block has one, else Type-I)
+ * whose expert_time is not smaller, else to the end.  Type-II tasks left at the
+ * end form a last block.  order_out[n_tasks]: task indices, highest priority
+ * first; block b covers positions [block_end_out[b-1], block_end_out[b]) with
+ * block_end_out[-1] = 0; block_end_out needs n_tasks entries.
+ * ZM_E_ARG for null pointers, expert indices outside [0, n_experts), costs that
+ * are negative or not finite, threads or shards < 1; ZM_E_NOMEM. */
+int zm_sched_build(const zm_sched_task *tasks, int n_tasks, const double *expert_time, int n_experts,
+                   const zm_sched_costs *costs, int32_t *order_out, int32_t *block_end_out, int *n_blocks_out);
+
+/* App. A: runs the tasks named by order[0 .. block_end[n_blocks-1]) (distinct
+ * task indices; tasks not named take no part) under work-conserving list
+ * scheduling in that priority order.  The I/O thread reads, block after block,
+ * the block's E-chunks in task order and then its SM-chunks in task order; a free
+ * decompression thread (the lowest-numbered of those free) takes the first
+ * decompression in (position, chunk) order whose E-chunk has arrived; the GPU
+ * stream takes the first ready recovery or execution, an execution ranking right
+ * behind its expert's last task.  result (may not be NULL) receives the totals,
+ * worker_end_out (may be NULL, L entries) each thread's last end, events_out
+ * (may be NULL) up to events_cap events in the order they were placed and
+ * n_events_out (may be NULL) how many there are in all.
+ * ZM_E_ARG as above and for a bad order; ZM_E_NOMEM. */
+int zm_sched_simulate(const zm_sched_task *tasks, int n_tasks, const double *expert_time, int n_experts,
+                      const zm_sched_costs *costs, const int32_t *order, const int32_t *block_end, int n_blocks,
+                      zm_sched_result *result, double *worker_end_out,
+                      zm_sched_event *events_out, size_t events_cap, size_t *n_events_out);
+
+/* App. B, lower bounds on the makespan of any schedule: bounds_out[0] = total
+ * read time, [1] = total decompression time / L, [2] = total execution time,
+ * [3] = longest chain of one task (reads, decompression on min(L, K) threads,
+ * recovery, its expert's execution). */
+int zm_sched_lower_bounds(const zm_sched_task *tasks, int n_tasks, const double *expert_time, int n_experts,
+                          const zm_sched_costs *costs, double bounds_out[4]);
+
 #ifdef __cplusplus
 }
 #endif

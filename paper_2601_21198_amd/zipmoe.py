@@ -24,7 +24,8 @@ EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codeb
            "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors",
            "zm_decode_exponents_host", "zm_recover", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_create",
            "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy", "zm_plan_selection_probabilities",
-           "zm_plan_hit_distribution", "zm_plan_makespan", "zm_plan_expected_makespan", "zm_plan_pools")
+           "zm_plan_hit_distribution", "zm_plan_makespan", "zm_plan_expected_makespan", "zm_plan_pools",
+           "zm_sched_build", "zm_sched_simulate", "zm_sched_lower_bounds")
 POOL_FULL, POOL_COMPRESSED, POOL_SM, POOL_E, POOL_NONE = 0, 1, 2, 3, 4
 
 
@@ -47,6 +48,32 @@ class CacheConfig(ctypes.Structure):
     """zm_cache_config"""
     _fields_ = [("n_experts", ctypes.c_int32), ("tensors_per_expert", ctypes.c_int32), ("slots", ctypes.c_int32 * 4),
                 ("tolerance", ctypes.c_int32), ("max_selected", ctypes.c_int32)]
+
+
+class SchedTask(ctypes.Structure):
+    """zm_sched_task"""
+    _fields_ = [("expert", ctypes.c_int32), ("needs_sm", ctypes.c_int32), ("needs_e", ctypes.c_int32),
+                ("needs_decode", ctypes.c_int32)]
+
+
+class SchedCosts(ctypes.Structure):
+    """zm_sched_costs"""
+    _fields_ = [("sm_read", ctypes.c_double), ("e_read", ctypes.c_double), ("decompress", ctypes.c_double),
+                ("recover", ctypes.c_double), ("threads", ctypes.c_int32), ("shards", ctypes.c_int32)]
+
+
+class SchedEvent(ctypes.Structure):
+    """zm_sched_event"""
+    _fields_ = [("kind", ctypes.c_int32), ("task", ctypes.c_int32), ("chunk", ctypes.c_int32), ("unit", ctypes.c_int32),
+                ("start", ctypes.c_double), ("end", ctypes.c_double)]
+
+
+class SchedResult(ctypes.Structure):
+    """zm_sched_result"""
+    _fields_ = [("makespan", ctypes.c_double), ("io_end", ctypes.c_double), ("charge", ctypes.c_double)]
+
+
+OP_E_READ, OP_SM_READ, OP_DECOMPRESS, OP_RECOVER, OP_EXECUTE = range(5)
 
 
 class PlanCosts(ctypes.Structure):
@@ -422,3 +449,55 @@ def plan_pools(f, k: int, costs: PlanCosts, memory_bytes: float, bytes_per_exper
                                _ptr(ba, ctypes.c_double), grid, pool_mask, _ptr(ratios, ctypes.c_double), slots,
                                ctypes.byref(cost)), "zm_plan_pools")
     return ratios.tolist(), list(slots), cost.value
+
+
+def _sched_args(tasks, expert_time):
+    arr = (SchedTask * max(1, len(tasks)))(*tasks)
+    pa = _dbl(expert_time)
+    return arr, len(tasks), _ptr(pa, ctypes.c_double), pa.size, pa
+
+
+def sched_build(tasks, expert_time, costs: SchedCosts):
+    """zm_sched_build: returns the blocks as lists of task indices, highest priority first."""
+    arr, n, pp, n_exp, keep = _sched_args(tasks, expert_time)
+    order = np.zeros(max(1, n), np.int32)
+    ends = np.zeros(max(1, n), np.int32)
+    n_blocks = ctypes.c_int(0)
+    _check(lib().zm_sched_build(arr, n, pp, n_exp, ctypes.byref(costs), _ptr(order, ctypes.c_int32),
+                                _ptr(ends, ctypes.c_int32), ctypes.byref(n_blocks)), "zm_sched_build")
+    blocks, at = [], 0
+    for b in range(n_blocks.value):
+        blocks.append(order[at:ends[b]].tolist())
+        at = int(ends[b])
+    return blocks
+
+
+def sched_simulate(tasks, expert_time, costs: SchedCosts, blocks, events: bool = True):
+    """zm_sched_simulate: returns (SchedResult, worker ends, list of SchedEvent)."""
+    arr, n, pp, n_exp, keep = _sched_args(tasks, expert_time)
+    order = np.array([j for b in blocks for j in b] or [0], np.int32)
+    ends = np.cumsum([len(b) for b in blocks] or [0]).astype(np.int32)
+    res = SchedResult()
+    worker_end = np.zeros(max(1, costs.threads))
+    n_events = ctypes.c_size_t(0)
+    L = lib()
+    _check(L.zm_sched_simulate(arr, n, pp, n_exp, ctypes.byref(costs), _ptr(order, ctypes.c_int32),
+                               _ptr(ends, ctypes.c_int32), len(blocks), ctypes.byref(res),
+                               _ptr(worker_end, ctypes.c_double), None, ctypes.c_size_t(0), ctypes.byref(n_events)),
+           "zm_sched_simulate")
+    if not events:
+        return res, worker_end.tolist(), []
+    ev = (SchedEvent * max(1, n_events.value))()
+    _check(L.zm_sched_simulate(arr, n, pp, n_exp, ctypes.byref(costs), _ptr(order, ctypes.c_int32),
+                               _ptr(ends, ctypes.c_int32), len(blocks), ctypes.byref(res),
+                               _ptr(worker_end, ctypes.c_double), ev, ctypes.c_size_t(n_events.value), None),
+           "zm_sched_simulate")
+    return res, worker_end.tolist(), list(ev[:n_events.value])
+
+
+def sched_lower_bounds(tasks, expert_time, costs: SchedCosts):
+    arr, n, pp, n_exp, keep = _sched_args(tasks, expert_time)
+    out = np.zeros(4)
+    _check(lib().zm_sched_lower_bounds(arr, n, pp, n_exp, ctypes.byref(costs), _ptr(out, ctypes.c_double)),
+           "zm_sched_lower_bounds")
+    return out.tolist()
