@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published peak HBM3E bandwidth
 # with: the entry is reported only while the source's hash still matches, else "traffic" is null.
 MEASURED_TRAFFIC = {
     "kernel_sha256_16": "eee453a96050effd",
-    "bytes_per_launch": {"cfg5": 119.07e6, "cfg4": 1216.26e6},
+    "bytes_per_launch": {"cfg5": 119.07e6, "cfg4": 1216.26e6, "cfg3": 173.17e6, "split-cfg4": 234.91e6},
 }
 
 
@@ -98,6 +98,20 @@ def cpu_baseline(sample_blobs, workers: int, min_seconds: float = 10.0):
     return 2.0 * total / dt / 1e9, total, dt, passes
 
 
+def reference_copy(mib: int) -> None:
+    """A plain device-to-device copy of known size, so that a profiler's byte counters read in the same run
+    can be scaled to bytes."""
+    if not mib:
+        return
+    import torch
+    src = torch.full((mib << 20,), 7, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_split(args, wl, workers: int, steps: int, warmup: int) -> int:
     """The paper's split on the first call's experts: host threads decompress the E-chunks (timed on the
     host), the recovery kernel merges exponent and sign-mantissa bytes resident in HBM (timed on the GPU)."""
@@ -126,6 +140,7 @@ def bench_split(args, wl, workers: int, steps: int, warmup: int) -> int:
             for de, ds, n, out in dev:
                 zm.recover(de.data_ptr(), ds.data_ptr(), n, out.data_ptr(), stream)
 
+    reference_copy(args.copy_mib)
     run(warmup)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -145,7 +160,8 @@ def bench_split(args, wl, workers: int, steps: int, warmup: int) -> int:
         "dtype": "u8", "data": "synthetic",
         "config": {"workload": wl.name, "path": "split", "tensors_per_step": len(dev), "values_per_step": n_total},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": "zm_recover_kernel",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic("split-" + args.workload),
+                     "kernel": "zm_recover_kernel",
                      "kernel_us": round(kernel_s * 1e6, 2), "algorithmic_bytes_per_launch": alg},
         "host_decode": {"value": round(2.0 * n_total / host_dt / 1e9, 3), "unit": "GB/s of bf16", "threads": workers,
                         "note": "zm_decode_exponents_host over the same tensors, one after the other"},
@@ -320,14 +336,7 @@ def main() -> int:
             for c in calls[s % n_distinct]:
                 c(stream)
 
-    if args.copy_mib:
-        src = torch.full((args.copy_mib << 20,), 7, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
+    reference_copy(args.copy_mib)
     run(0, warmup)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
