@@ -227,3 +227,27 @@ def test_serialised_format_is_stable():
         assert hashlib.sha256(ref.tobytes()).hexdigest() == digest
         mine, _ = zm.encode(w, int(C), int(W), lengths)
         assert hashlib.sha256(mine.tobytes()).hexdigest() == digest
+
+
+def test_missing_library_is_an_error_not_a_fallback():
+    # the product path has no CPU fallback: without the built library every call fails at load time
+    import subprocess
+    import sys
+    env = dict(os.environ, ZIPMOE_LIBRARY="/nonexistent/libzipmoe.so")
+    code = ("import numpy as np\n"
+            "from paper_2601_21198_amd import zipmoe as zm\n"
+            "zm.compress(np.zeros(4096, np.uint16), 4096)\n")
+    r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, env=env, capture_output=True, text=True)
+    assert r.returncode != 0 and "is not built" in r.stderr
+
+
+def test_product_sources_do_not_touch_the_reference_codec():
+    # the reference implementations are test infrastructure: nothing in the package imports, opens or links them
+    pkg = os.path.join(ROOT, "paper_2601_21198_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"\boracle\b|zm_oracle|libzm_oracle", text), os.path.join(dirpath, f)
+    text = open(os.path.join(ROOT, "include", "zipmoe.h")).read()
+    assert not re.search(r"zm_oracle|libzm_oracle", text)
