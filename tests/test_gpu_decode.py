@@ -76,6 +76,31 @@ def test_all_bit_patterns_and_duplicates():
     assert np.array_equal(got[0], zo.decode(blob12))
 
 
+def test_mixed_geometries_in_one_call():
+    # tensors with different chunk lengths, stream lengths and code-length limits share a call: both round
+    # lengths are launched, and the staging area is sized for the longest stream of each group.  Every other
+    # blob comes from the reference encoder.
+    rng = np.random.default_rng(77)
+    geometries = [(4096, 512, 8), (4096, 4096, 8), (16384, 4096, 8), (16384, 2048, 11), (8192, 8192, 9),
+                  (2048, 1024, 12), (16384, 16384, 8), (1024, 512, 10)]
+    tensors, blobs = [], []
+    for i in range(48):
+        C, W, max_len = geometries[int(rng.integers(len(geometries)))]
+        kind = KINDS[int(rng.integers(len(KINDS)))]
+        n = int(rng.integers(1, 70000))
+        w = synth.special_tensor(kind, n, seed=1000 + i)
+        if i % 2:
+            blob = zo.encode(w, C, W, zo.code_lengths(zo.histogram(zo.split(w)[0]), max_len))
+        else:
+            blob, _ = zm.compress(w, C, W, max_len)
+        tensors.append(w)
+        blobs.append(blob)
+    say(f"mixed geometries: {len(blobs)} tensors in one call")
+    got = gpu_decode_tensors(blobs)
+    for w, blob, g in zip(tensors, blobs, got):
+        assert np.array_equal(g, w) and np.array_equal(g, zo.decode(blob))
+
+
 def test_bad_arguments_are_refused_on_the_host():
     import torch
     w = synth.special_tensor("gauss", 5000, 0)
