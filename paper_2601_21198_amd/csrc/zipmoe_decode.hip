@@ -169,8 +169,9 @@ template <int R, int kWaves, bool kStreaming>
 __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
 {
     // Byte tables of the workgroup's tensor, at fixed LDS addresses so that a lookup is one LDS read with
-    // an immediate offset.  With 256 entries a table spans each of the 64 banks once: lanes either read
-    // the same word (broadcast) or different banks, so lookups never conflict.
+    // an immediate offset.  The lookups of a wave hit random words of a 64-word table and do collide on
+    // banks (the counters show conflicts in 45 % of the LDS-active cycles), but waves spend about 1 % of
+    // their cycles waiting for LDS: confining the lookups to 32- or 16-word tables changed nothing.
     __shared__ __align__(16) uint8_t len_tab[Code<R>::kEntries];
     __shared__ __align__(16) uint8_t sym_tab[Code<R>::kEntries];
     extern __shared__ __align__(16) uint32_t stream_lds[];
@@ -416,8 +417,10 @@ int launch_group(const Task *tasks, int n, hipStream_t stream)
         const size_t cap = stream_cap_words(max_stream, kLenBound);
         L.stream_cap_words = static_cast<uint32_t>(cap);
         // two streams per workgroup: measured on one MoE layer call of 118 MB, 1 / 2 / 4 / 8 waves per
-        // workgroup reach 63.1 / 63.2 / 61.9 / 58.2 % of the HBM roofline (1.2 GB calls: 72.5 / 72.9 / 73.2 / 72.0 %)
-        const int rc = launch_tasks<R, 2>(L, cap, stream);
+        // workgroup reach 63.1 / 63.2 / 61.9 / 58.2 % of the HBM roofline (1.2 GB calls: 72.5 / 72.9 / 73.2 / 72.0 %).
+        // With long codes a workgroup stages 8 KiB of tables, so four streams share them: 2 / 4 / 8 waves reach
+        // 41.9 / 45.6 / 45.6 % on a 170 MB call and 52.2 / 53.8 / 52.9 % on 1.2 GB calls.
+        const int rc = launch_tasks<R, R == 4 ? 2 : 4>(L, cap, stream);
         if (rc != ZM_OK) return rc;
         done += k;
     }
