@@ -249,9 +249,10 @@ void package_merge(const std::vector<uint64_t> &weight, int max_len, std::vector
 // Table-driven decode of one woven stream on the host: the 64 lanes are walked round by round exactly
 // as the lock-step GPU decoder does, each lane with a 64-bit window over its own two current words.
 // lut: 2^max_len entries (symbol | length << 8).  Returns false if the stream runs out of words.
-bool unweave_stream(const uint32_t *words, size_t n_words, uint32_t n, const uint8_t *lut, uint32_t max_len,
+bool unweave_stream(const uint8_t *stream, size_t n_words, uint32_t n, const uint8_t *lut, uint32_t max_len,
                     uint8_t *e)
 {
+    auto word = [stream](size_t i) { return load_le<uint32_t>(stream + 4 * i); };
     const uint32_t R = round_symbols_for(max_len);
     const uint32_t tiles = (n + kTile - 1) / kTile;
     const uint32_t rounds = tiles * kRun / R;
@@ -260,7 +261,7 @@ bool unweave_stream(const uint32_t *words, size_t n_words, uint32_t n, const uin
     uint64_t window[kLanes];      // bits of the lane's stream from its current word on
     uint32_t pos[kLanes];         // bits of the current word already used
     for (uint32_t lane = 0; lane < kLanes; ++lane) {
-        window[lane] = words[2 * lane] | (static_cast<uint64_t>(words[2 * lane + 1]) << 32);
+        window[lane] = word(2 * lane) | (static_cast<uint64_t>(word(2 * lane + 1)) << 32);
         pos[lane] = 0;
     }
     size_t next = 2 * kLanes;
@@ -283,7 +284,7 @@ bool unweave_stream(const uint32_t *words, size_t n_words, uint32_t n, const uin
         for (uint32_t lane = 0; lane < kLanes; ++lane) {
             if (pos[lane] >= 32) {
                 if (next >= n_words) return false;
-                window[lane] = (window[lane] >> 32) | (static_cast<uint64_t>(words[next++]) << 32);
+                window[lane] = (window[lane] >> 32) | (static_cast<uint64_t>(word(next++)) << 32);
                 pos[lane] -= 32;
             }
         }
@@ -291,7 +292,9 @@ bool unweave_stream(const uint32_t *words, size_t n_words, uint32_t n, const uin
     return true;
 }
 
-int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, uint64_t c, uint8_t *e_out)
+// lut: the decode table built from the blob's code lengths (not the blob's own copy, which a caller may not
+// have validated: its lengths bound the shifts below)
+int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, const uint8_t *lut, uint64_t c, uint8_t *e_out)
 {
     const uint8_t *entry = p + t.table_offset + static_cast<uint64_t>(t.table_stride) * c;
     const uint64_t ent = load_le<uint64_t>(entry);
@@ -313,8 +316,7 @@ int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, uint64_t c
         const uint32_t o0 = load_le<uint32_t>(entry + 8 + 4 * s), o1 = load_le<uint32_t>(entry + 8 + 4 * (s + 1));
         if ((o0 & 3) || o1 < o0 || o1 > end - at) return ZM_E_FORMAT;
         const uint32_t sn = std::min(t.stream_values, cn - s * t.stream_values);
-        if (!unweave_stream(reinterpret_cast<const uint32_t *>(h + o0), (o1 - o0) / 4, sn, p + t.lut_offset, t.max_len,
-                            e + static_cast<size_t>(s) * t.stream_values))
+        if (!unweave_stream(h + o0, (o1 - o0) / 4, sn, lut, t.max_len, e + static_cast<size_t>(s) * t.stream_values))
             return ZM_E_FORMAT;
     }
     return ZM_OK;
@@ -535,8 +537,8 @@ int zm_decode_exponents_host(const void *blob_host, size_t size, uint32_t chunk_
 {
     if (!blob_host || !e_out) return ZM_E_ARG;
     const uint8_t *p = static_cast<const uint8_t *>(blob_host);
-    zm_tensor_info t;
-    const int rc = read_info(p, size, &t, nullptr);
+    zm_tensor_info t; Book book;
+    const int rc = read_info(p, size, &t, &book);
     if (rc != ZM_OK) return rc;
     if (t.blob_size > size) return ZM_E_FORMAT;
     if (chunk_begin > chunk_end || chunk_end > t.n_chunks) return ZM_E_ARG;
@@ -544,20 +546,30 @@ int zm_decode_exponents_host(const void *blob_host, size_t size, uint32_t chunk_
     const uint32_t workers = std::min<uint32_t>(std::max(n_threads, 1), chunk_end - chunk_begin);
     std::atomic<uint32_t> next_chunk{chunk_begin};
     std::atomic<int> status{ZM_OK};
-    auto work = [&]() {
-        for (;;) {
-            const uint32_t c = next_chunk.fetch_add(1);
-            if (c >= chunk_end || status.load() != ZM_OK) return;
-            const int r = decode_chunk_exponents(p, t, c, e_out);
-            if (r != ZM_OK) status.store(r);
-        }
-    };
+    std::vector<std::thread> pool;
     try {
-        std::vector<std::thread> pool;
-        for (uint32_t i = 1; i < workers; ++i) pool.emplace_back(work);
+        std::vector<uint8_t> lut(2u << t.max_len);
+        fill_decode_table(book, lut.data());
+        auto work = [&]() {
+            for (;;) {
+                const uint32_t c = next_chunk.fetch_add(1);
+                if (c >= chunk_end || status.load() != ZM_OK) return;
+                const int r = decode_chunk_exponents(p, t, lut.data(), c, e_out);
+                if (r != ZM_OK) status.store(r);
+            }
+        };
+        try {
+            pool.reserve(workers);
+            for (uint32_t i = 1; i < workers; ++i) pool.emplace_back(work);
+        } catch (...) {
+            status.store(ZM_E_NOMEM);                  // the threads that did start see it and stop
+        }
         work();
         for (auto &th : pool) th.join();
-    } catch (...) { return ZM_E_NOMEM; }
+    } catch (...) {
+        for (auto &th : pool) if (th.joinable()) th.join();
+        return ZM_E_NOMEM;
+    }
     return status.load();
 }
 

@@ -251,3 +251,19 @@ def test_product_sources_do_not_touch_the_reference_codec():
                 assert not re.search(r"\boracle\b|zm_oracle|libzm_oracle", text), os.path.join(dirpath, f)
     text = open(os.path.join(ROOT, "include", "zipmoe.h")).read()
     assert not re.search(r"zm_oracle|libzm_oracle", text)
+
+
+def test_host_decoder_does_not_trust_the_blobs_decode_table():
+    # the table copy inside the blob serves the GPU; the host decoder rebuilds its own from the code lengths,
+    # so a damaged copy (which zm_validate_blob reports) cannot send it astray
+    w = synth.special_tensor("gauss", 20000, 5)
+    blob, _ = zm.compress(w, 4096, 1024, 8)
+    info = zm.blob_info(blob[:384])
+    bad = blob.copy()
+    bad[info.lut_offset: info.lut_offset + 512] = 0xFF          # lengths of 255 bits everywhere
+    with pytest.raises(zm.ZipMoEError):
+        zm.validate_blob(bad)
+    assert np.array_equal(zm.decode_exponents_host(bad, n_threads=3), zo.split(w)[0])
+    unaligned = np.zeros(blob.size + 1, np.uint8)[1:]            # a host copy at an odd address
+    unaligned[:] = blob
+    assert np.array_equal(zm.decode_exponents_host(unaligned, n_threads=2), zo.split(w)[0])
