@@ -603,9 +603,10 @@ int zo_decode(const uint8_t *blob, size_t size, uint16_t *out, size_t out_cap)
 int zo_check_table(const uint8_t *blob, size_t size)
 {
     if (size < 384 || get32(blob + H_MAGIC) != ZO_MAGIC) return ZO_E_FORMAT;
-    const uint8_t *len = blob + get64(blob + H_LEN_OFF);
+    if (get64(blob + H_LEN_OFF) != ZO_HEADER_BYTES || get64(blob + H_LUT_OFF) != ZO_HEADER_BYTES + 256) return ZO_E_FORMAT;
+    const uint8_t *len = blob + ZO_HEADER_BYTES;
     int L = (int)get32(blob + H_L);
-    uint64_t lut_off = get64(blob + H_LUT_OFF);
+    uint64_t lut_off = ZO_HEADER_BYTES + 256;
     if (L < 1 || L > ZO_MAX_LEN || lut_off + 2 * ((uint64_t)1 << L) > size) return ZO_E_FORMAT;
     uint16_t code[256];
     zo_canonical(len, code);
