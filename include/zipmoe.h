@@ -272,7 +272,10 @@ int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs
  * all other pointers are valid until the next fetch on this cache.  Work the
  * caller queued on `stream` before the call (readers of earlier results) is
  * waited for before anything is overwritten.  Not thread-safe per cache.
- * ZM_E_ARG for bad ids, duplicates or too many experts; ZM_E_HIP. */
+ * ZM_E_ARG for bad ids, duplicates or too many experts (the cache is unchanged);
+ * ZM_E_HIP if a copy, an event or a launch fails: the pools may then disagree
+ * with the bookkeeping, so every later fetch on this cache returns ZM_E_HIP too
+ * and the cache can only be destroyed. */
 int zm_cache_fetch(zm_cache *cache, const int32_t *expert_ids, int n_selected, void **out_bf16,
                    int32_t *found_in, void *stream);
 

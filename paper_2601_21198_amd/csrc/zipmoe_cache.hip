@@ -131,6 +131,7 @@ struct zm_cache {
     std::vector<int32_t> limbo[kPools];        // slots released by the current fetch, reusable from the next one
     hipStream_t copy_stream = nullptr;
     hipEvent_t ev_start = nullptr, ev_copied = nullptr;
+    bool broken = false;                       // a fetch failed half-way: slots and bookkeeping may disagree
 
     uint8_t *slot_ptr(int pool, int slot) const { return arena + lay.pool_off[pool] + lay.slot_bytes[pool] * static_cast<size_t>(slot); }
     uint8_t *transient_ptr(int j) const { return arena + lay.transient_off + lay.transient_bytes * static_cast<size_t>(j); }
@@ -219,6 +220,7 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
                    void *stream)
 {
     if (!c || !expert_ids || !out_bf16 || n_selected < 0 || n_selected > c->cfg.max_selected) return ZM_E_ARG;
+    if (c->broken) return ZM_E_HIP;
     if (n_selected == 0) return ZM_OK;
     const int T = c->cfg.tensors_per_expert, N = c->cfg.n_experts;
     for (int j = 0; j < n_selected; ++j) {
@@ -317,7 +319,7 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
             if (sm_dst) {
                 const hipError_t rc = sm_src ? hipMemcpyAsync(sm_dst, sm_src, sm_len, hipMemcpyDeviceToDevice, c->copy_stream)
                                              : hipMemcpyAsync(sm_dst, c->host[i] + ti.sm_offset, sm_len, hipMemcpyHostToDevice, c->copy_stream);
-                if (rc != hipSuccess) return ZM_E_HIP;
+                if (rc != hipSuccess) { c->broken = true; return ZM_E_HIP; }
                 copied = true;
             }
             const uint8_t *e_src = have_e ? have_e + c->lay.e_off[m] : nullptr;
@@ -325,7 +327,7 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
             if (e_dst) {
                 const hipError_t rc = e_src ? hipMemcpyAsync(e_dst, e_src, e_len, hipMemcpyDeviceToDevice, c->copy_stream)
                                             : hipMemcpyAsync(e_dst, c->host[i] + ti.e_offset, e_len, hipMemcpyHostToDevice, c->copy_stream);
-                if (rc != hipSuccess) return ZM_E_HIP;
+                if (rc != hipSuccess) { c->broken = true; return ZM_E_HIP; }
                 copied = true;
             }
             zm_tensor_parts pt;
@@ -340,12 +342,12 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
     }
     // experts whose parts are all resident decode while the copies for the others are in flight
     int rc = zm_decode_tensors(parts_now, infos_now, n_now, out_now, stream);
-    if (rc != ZM_OK) return rc;
-    if (any_copy) {
+    if (rc == ZM_OK && any_copy) {
         if (hipEventRecord(c->ev_copied, c->copy_stream) != hipSuccess ||
-            hipStreamWaitEvent(main_stream, c->ev_copied, 0) != hipSuccess) return ZM_E_HIP;
-        rc = zm_decode_tensors(parts_later, infos_later, n_later, out_later, stream);
+            hipStreamWaitEvent(main_stream, c->ev_copied, 0) != hipSuccess) rc = ZM_E_HIP;
+        else rc = zm_decode_tensors(parts_later, infos_later, n_later, out_later, stream);
     }
+    if (rc != ZM_OK) c->broken = true;
     return rc;
 }
 
