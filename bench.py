@@ -406,10 +406,13 @@ def main() -> int:
     }
     if not args.no_cpu_baseline:
         gbps, n, dt, passes = cpu_baseline(sample_blobs, workers)
+        one_gbps, one_n, one_dt, _ = cpu_baseline(sample_blobs[:1], 1, min_seconds=3.0)
         result["cpu_baseline"] = {
             "value": round(gbps, 4), "unit": "GB/s", "cores": workers, "kind": "oracle",
             "sample": f"the {len(sample_blobs)} tensors of the first call's routed experts, {passes} passes, "
                       f"{n} values decoded in {dt:.1f} s",
+            "single_thread": {"value": round(one_gbps, 4), "unit": "GB/s", "cores": 1,
+                              "sample": f"the first of these tensors, {one_n} values decoded in {one_dt:.1f} s"},
         }
     print(json.dumps(result), flush=True)
     return 0
