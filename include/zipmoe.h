@@ -248,16 +248,33 @@ int zm_cache_dispatch(const uint64_t *counts, int n_experts, const int32_t slots
  * array [n_experts * tensors_per_expert] from zm_blob_info. */
 int zm_cache_arena_bytes(const zm_cache_config *config, const zm_tensor_info *infos, size_t *bytes);
 
+/* Bytes of one expert's packed host image (below). */
+int zm_cache_image_bytes(const zm_cache_config *config, const zm_tensor_info *infos, size_t *bytes);
+
+/* Packs what the cache ever copies of one expert -- the SM sections of its
+ * tensors, then their E-chunk regions, laid out as in a pool slot -- into
+ * `image` (HOST memory of zm_cache_image_bytes bytes, pinned for asynchronous
+ * copies).  With such images a fetch moves an expert's missing parts with one
+ * copy (both parts) or one per part instead of one per tensor and part; each
+ * host-to-device copy has a fixed cost of some 10 us.  host_blobs: as for
+ * zm_cache_create.  ZM_E_ARG, ZM_E_SIZE. */
+int zm_cache_pack_expert(const zm_cache_config *config, const zm_tensor_info *infos, const void *const *host_blobs,
+                         int expert, void *image, size_t image_bytes);
+
 /* Creates a cache.  host_blobs: host array [n_experts * tensors_per_expert] of
- * HOST pointers to the validated blobs (pinned memory makes the copies
- * asynchronous); they must stay valid for the life of the cache.  arena: DEVICE
+ * HOST pointers to the validated blobs.  host_images: NULL, or host array
+ * [n_experts] of images made by zm_cache_pack_expert.  Without images the blobs
+ * are what fetches copy from (pinned memory makes the copies asynchronous) and
+ * must stay valid for the life of the cache; with images the images must, and
+ * the blobs are only read during this call.  arena: DEVICE
  * memory of at least zm_cache_arena_bytes bytes, 256-byte aligned, owned by the
  * caller and used by the cache until zm_cache_destroy.  The decode tables and
  * chunk tables of all tensors are uploaded at once (the call returns when they
  * are resident); all pools start empty.  The cache creates one HIP stream and two
  * events of its own and allocates no device memory.
  * ZM_E_ARG, ZM_E_SIZE (arena too small), ZM_E_NOMEM, ZM_E_HIP. */
-int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs, const zm_tensor_info *infos,
+int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs, const void *const *host_images,
+                    const zm_tensor_info *infos,
                     void *arena, size_t arena_bytes, zm_cache **out);
 
 /* Makes the bf16 tensors of the named experts available and tells where they are.

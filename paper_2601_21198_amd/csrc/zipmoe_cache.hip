@@ -122,7 +122,8 @@ struct zm_cache {
     zm_cache_config cfg;
     Layout lay;
     std::vector<zm_tensor_info> infos;
-    std::vector<const uint8_t *> host;
+    std::vector<const uint8_t *> host;         // per tensor: the blob (used by fetches only when there are no images)
+    std::vector<const uint8_t *> image;        // per expert: packed SM sections then E-chunk regions, or empty
     uint8_t *arena = nullptr;
     std::vector<uint64_t> count;
     std::vector<int8_t> pool_of;               // per expert: pool or kUncached
@@ -154,7 +155,37 @@ int zm_cache_arena_bytes(const zm_cache_config *config, const zm_tensor_info *in
     return ZM_OK;
 }
 
-int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs, const zm_tensor_info *infos,
+int zm_cache_image_bytes(const zm_cache_config *config, const zm_tensor_info *infos, size_t *bytes)
+{
+    if (!config_ok(config) || !infos || !bytes) return ZM_E_ARG;
+    Layout L;
+    try { if (!make_layout(*config, infos, L)) return ZM_E_ARG; } catch (const std::bad_alloc &) { return ZM_E_NOMEM; }
+    *bytes = L.sm_bytes + L.e_bytes;
+    return ZM_OK;
+}
+
+int zm_cache_pack_expert(const zm_cache_config *config, const zm_tensor_info *infos, const void *const *host_blobs,
+                         int expert, void *image, size_t image_bytes)
+{
+    if (!config_ok(config) || !infos || !host_blobs || !image || expert < 0 || expert >= config->n_experts) return ZM_E_ARG;
+    Layout L;
+    try { if (!make_layout(*config, infos, L)) return ZM_E_ARG; } catch (const std::bad_alloc &) { return ZM_E_NOMEM; }
+    if (image_bytes < L.sm_bytes + L.e_bytes) return ZM_E_SIZE;
+    uint8_t *dst = static_cast<uint8_t *>(image);
+    std::memset(dst, 0, L.sm_bytes + L.e_bytes);
+    for (int m = 0; m < config->tensors_per_expert; ++m) {
+        const size_t i = static_cast<size_t>(expert) * config->tensors_per_expert + m;
+        const zm_tensor_info &t = infos[i];
+        if (!host_blobs[i]) return ZM_E_ARG;
+        const uint8_t *src = static_cast<const uint8_t *>(host_blobs[i]);
+        std::memcpy(dst + L.sm_off[m], src + t.sm_offset, t.e_offset - t.sm_offset);
+        std::memcpy(dst + L.sm_bytes + L.e_off[m], src + t.e_offset, t.blob_size - t.e_offset);
+    }
+    return ZM_OK;
+}
+
+int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs, const void *const *host_images,
+                    const zm_tensor_info *infos,
                     void *arena, size_t arena_bytes, zm_cache **out)
 {
     if (!config_ok(config) || !host_blobs || !infos || !arena || !out) return ZM_E_ARG;
@@ -171,6 +202,13 @@ int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs
         for (size_t i = 0; i < n; ++i) {
             if (!host_blobs[i]) { delete c; return ZM_E_ARG; }
             c->host[i] = static_cast<const uint8_t *>(host_blobs[i]);
+        }
+        if (host_images) {
+            c->image.resize(config->n_experts);
+            for (int e = 0; e < config->n_experts; ++e) {
+                if (!host_images[e]) { delete c; return ZM_E_ARG; }
+                c->image[e] = static_cast<const uint8_t *>(host_images[e]);
+            }
         }
         c->arena = static_cast<uint8_t *>(arena);
         c->count.assign(config->n_experts, 0);
@@ -306,17 +344,38 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
             else if (pl.target == ZM_POOL_SM) keep_sm = dst;
             else if (pl.target == ZM_POOL_E) keep_e = dst;
         }
+        // With packed images the parts of an expert move as whole regions: one copy when both regions come
+        // from the host and land next to each other (a C slot, or the transient buffer), else one per region.
+        const bool by_region = !c->image.empty() && pl.found != ZM_POOL_FULL;
+        bool region_copied = false;
+        if (by_region) {
+            uint8_t *sm_to = keep_sm ? keep_sm : (have_sm ? nullptr : tr_sm);
+            uint8_t *e_to = keep_e ? keep_e : (have_e ? nullptr : tr_e);
+            const uint8_t *img = c->image[e];
+            hipError_t rc = hipSuccess;
+            if (sm_to && e_to && !have_sm && !have_e && e_to == sm_to + c->lay.sm_bytes) {
+                rc = hipMemcpyAsync(sm_to, img, c->lay.sm_bytes + c->lay.e_bytes, hipMemcpyHostToDevice, c->copy_stream);
+            } else {
+                if (sm_to) rc = have_sm ? hipMemcpyAsync(sm_to, have_sm, c->lay.sm_bytes, hipMemcpyDeviceToDevice, c->copy_stream)
+                                        : hipMemcpyAsync(sm_to, img, c->lay.sm_bytes, hipMemcpyHostToDevice, c->copy_stream);
+                if (rc == hipSuccess && e_to)
+                    rc = have_e ? hipMemcpyAsync(e_to, have_e, c->lay.e_bytes, hipMemcpyDeviceToDevice, c->copy_stream)
+                                : hipMemcpyAsync(e_to, img + c->lay.sm_bytes, c->lay.e_bytes, hipMemcpyHostToDevice, c->copy_stream);
+            }
+            if (rc != hipSuccess) { c->broken = true; return ZM_E_HIP; }
+            region_copied = sm_to || e_to;
+        }
         for (int m = 0; m < T; ++m) {
             const size_t i = static_cast<size_t>(e) * T + m;
             const zm_tensor_info &ti = c->infos[i];
             void *&out = out_bf16[static_cast<size_t>(j) * T + m];
             if (pl.found == ZM_POOL_FULL) { out = c->slot_ptr(ZM_POOL_FULL, pl.slot) + c->lay.full_off[m]; continue; }
-            bool copied = false;
+            bool copied = region_copied;
             const size_t sm_len = ti.e_offset - ti.sm_offset, e_len = ti.blob_size - ti.e_offset;
             // SM part: already in place, or moved device-to-device into its new pool, or fetched from the host
             const uint8_t *sm_src = have_sm ? have_sm + c->lay.sm_off[m] : nullptr;
             uint8_t *sm_dst = keep_sm ? keep_sm + c->lay.sm_off[m] : (sm_src ? nullptr : tr_sm + c->lay.sm_off[m]);
-            if (sm_dst) {
+            if (sm_dst && !by_region) {
                 const hipError_t rc = sm_src ? hipMemcpyAsync(sm_dst, sm_src, sm_len, hipMemcpyDeviceToDevice, c->copy_stream)
                                              : hipMemcpyAsync(sm_dst, c->host[i] + ti.sm_offset, sm_len, hipMemcpyHostToDevice, c->copy_stream);
                 if (rc != hipSuccess) { c->broken = true; return ZM_E_HIP; }
@@ -324,7 +383,7 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
             }
             const uint8_t *e_src = have_e ? have_e + c->lay.e_off[m] : nullptr;
             uint8_t *e_dst = keep_e ? keep_e + c->lay.e_off[m] : (e_src ? nullptr : tr_e + c->lay.e_off[m]);
-            if (e_dst) {
+            if (e_dst && !by_region) {
                 const hipError_t rc = e_src ? hipMemcpyAsync(e_dst, e_src, e_len, hipMemcpyDeviceToDevice, c->copy_stream)
                                             : hipMemcpyAsync(e_dst, c->host[i] + ti.e_offset, e_len, hipMemcpyHostToDevice, c->copy_stream);
                 if (rc != hipSuccess) { c->broken = true; return ZM_E_HIP; }

@@ -22,7 +22,8 @@ MODE_CODED, MODE_RAW = 0, 1
 
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
            "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors",
-           "zm_decode_exponents_host", "zm_recover", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_create",
+           "zm_decode_exponents_host", "zm_recover", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_image_bytes",
+           "zm_cache_pack_expert", "zm_cache_create",
            "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy", "zm_plan_selection_probabilities",
            "zm_plan_hit_distribution", "zm_plan_makespan", "zm_plan_expected_makespan", "zm_plan_pools",
            "zm_sched_build", "zm_sched_simulate", "zm_sched_lower_bounds")
@@ -120,7 +121,11 @@ def lib() -> ctypes.CDLL:
         L.zm_recover.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
         L.zm_cache_dispatch.argtypes = [u64p, c.c_int, c.POINTER(c.c_int32), c.c_int, c.c_int]
         L.zm_cache_arena_bytes.argtypes = [c.POINTER(CacheConfig), c.POINTER(TensorInfo), c.POINTER(c.c_size_t)]
-        L.zm_cache_create.argtypes = [c.POINTER(CacheConfig), c.POINTER(c.c_void_p), c.POINTER(TensorInfo), c.c_void_p,
+        L.zm_cache_image_bytes.argtypes = [c.POINTER(CacheConfig), c.POINTER(TensorInfo), c.POINTER(c.c_size_t)]
+        L.zm_cache_pack_expert.argtypes = [c.POINTER(CacheConfig), c.POINTER(TensorInfo), c.POINTER(c.c_void_p), c.c_int,
+                                           c.c_void_p, c.c_size_t]
+        L.zm_cache_create.argtypes = [c.POINTER(CacheConfig), c.POINTER(c.c_void_p), c.POINTER(c.c_void_p),
+                                      c.POINTER(TensorInfo), c.c_void_p,
                                       c.c_size_t, c.POINTER(c.c_void_p)]
         L.zm_cache_fetch.argtypes = [c.c_void_p, c.POINTER(c.c_int32), c.c_int, c.POINTER(c.c_void_p),
                                      c.POINTER(c.c_int32), c.c_void_p]
@@ -349,31 +354,50 @@ class ExpertCache:
     marshals zm_cache_fetch.  The policy and all data movement are the library's."""
 
     def __init__(self, expert_blobs: Sequence[Sequence[np.ndarray]], slots, tolerance: int, max_selected: int,
-                 device: str = "cuda:0"):
+                 device: str = "cuda:0", packed: bool = True):
+        """packed: keep one pinned image per expert (zm_cache_pack_expert) so that a fetch copies an expert's
+        missing parts in one or two pieces; else the pinned blobs themselves are the tier below HBM."""
         import torch
         self.n_experts = len(expert_blobs)
         self.tensors_per_expert = len(expert_blobs[0])
         n = self.n_experts * self.tensors_per_expert
         self.infos = (TensorInfo * n)()
-        self.host = []                       # pinned copies of the blobs: the tier below HBM
+        self.host = []                       # pinned host memory: the tier below HBM
         ptrs = (ctypes.c_void_p * n)()
+        flat = []
         k = 0
         for tensors in expert_blobs:
             for blob in tensors:
                 validate_blob(blob)
                 self.infos[k] = blob_info(blob[:384])
-                pinned = torch.empty(blob.size, dtype=torch.uint8, pin_memory=True)
-                pinned.numpy()[:] = blob
-                self.host.append(pinned)
-                ptrs[k] = pinned.data_ptr()
+                if packed:
+                    blob = np.ascontiguousarray(blob)
+                    flat.append(blob)
+                    ptrs[k] = blob.ctypes.data
+                else:
+                    pinned = torch.empty(blob.size, dtype=torch.uint8, pin_memory=True)
+                    pinned.numpy()[:] = blob
+                    self.host.append(pinned)
+                    ptrs[k] = pinned.data_ptr()
                 k += 1
         self.config = CacheConfig(self.n_experts, self.tensors_per_expert, (ctypes.c_int32 * 4)(*[int(x) for x in slots]),
                                   tolerance, max_selected)
+        images = None
+        if packed:
+            size = ctypes.c_size_t(0)
+            _check(lib().zm_cache_image_bytes(ctypes.byref(self.config), self.infos, ctypes.byref(size)), "zm_cache_image_bytes")
+            images = (ctypes.c_void_p * self.n_experts)()
+            for e in range(self.n_experts):
+                pinned = torch.empty(size.value, dtype=torch.uint8, pin_memory=True)
+                _check(lib().zm_cache_pack_expert(ctypes.byref(self.config), self.infos, ptrs, e,
+                                                  ctypes.c_void_p(pinned.data_ptr()), size.value), "zm_cache_pack_expert")
+                self.host.append(pinned)
+                images[e] = pinned.data_ptr()
         need = ctypes.c_size_t(0)
         _check(lib().zm_cache_arena_bytes(ctypes.byref(self.config), self.infos, ctypes.byref(need)), "zm_cache_arena_bytes")
         self.arena = torch.empty(need.value, dtype=torch.uint8, device=device)
         handle = ctypes.c_void_p()
-        _check(lib().zm_cache_create(ctypes.byref(self.config), ptrs, self.infos, self.arena.data_ptr(), need.value,
+        _check(lib().zm_cache_create(ctypes.byref(self.config), ptrs, images, self.infos, self.arena.data_ptr(), need.value,
                                      ctypes.byref(handle)), "zm_cache_create")
         self.handle = handle
         self.max_selected = max_selected

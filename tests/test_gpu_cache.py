@@ -81,12 +81,13 @@ def read_back(cache, ptr, n):
 
 @pytest.mark.parametrize("slots,tolerance", [((2, 3, 3, 3), 1), ((0, 0, 0, 0), 0), ((3, 0, 0, 0), 0), ((0, 4, 0, 0), 2),
                                              ((0, 0, 4, 0), 0), ((0, 0, 0, 4), 0), ((1, 1, 1, 1), 0), ((16, 0, 0, 0), 0)])
-def test_fetch_is_bit_exact_in_every_state_and_follows_the_policy(slots, tolerance):
+@pytest.mark.parametrize("packed", [True, False])
+def test_fetch_is_bit_exact_in_every_state_and_follows_the_policy(slots, tolerance, packed):
     import torch
     n_experts, k = 16, 4
     shapes = (20000, 12345, 4096)
     tensors, blobs = make_layer(n_experts, shapes, seed=sum(slots) + tolerance)
-    cache = zm.ExpertCache(blobs, slots, tolerance, max_selected=k)
+    cache = zm.ExpertCache(blobs, slots, tolerance, max_selected=k, packed=packed)
     model = PolicyModel(n_experts, slots, tolerance)
     stream = torch.cuda.current_stream().cuda_stream
     rng = np.random.default_rng(7)
@@ -126,14 +127,15 @@ def test_fetch_refuses_bad_requests():
     cache.close()
 
 
-def test_back_to_back_fetches_without_host_synchronisation():
+@pytest.mark.parametrize("packed", [True, False])
+def test_back_to_back_fetches_without_host_synchronisation(packed):
     """fetches and their consumers are only ordered by the stream: each fetch's outputs are copied away by
     work queued on the same stream, the next fetch follows at once, everything is checked at the end"""
     import torch
     n_experts, k = 12, 3
     shapes = (30000, 8192)
     tensors, blobs = make_layer(n_experts, shapes, seed=11)
-    cache = zm.ExpertCache(blobs, (2, 2, 2, 2), 1, max_selected=k)
+    cache = zm.ExpertCache(blobs, (2, 2, 2, 2), 1, max_selected=k, packed=packed)
     stream = torch.cuda.current_stream().cuda_stream
     rng = np.random.default_rng(3)
     steps = 60

@@ -267,3 +267,43 @@ def test_host_decoder_does_not_trust_the_blobs_decode_table():
     unaligned = np.zeros(blob.size + 1, np.uint8)[1:]            # a host copy at an odd address
     unaligned[:] = blob
     assert np.array_equal(zm.decode_exponents_host(unaligned, n_threads=2), zo.split(w)[0])
+
+
+def test_packed_expert_image_layout():
+    # zm_cache_pack_expert: the SM sections of an expert's tensors, then their E-chunk regions, each at the
+    # offset the largest expert's tensor of that index needs (256-byte aligned), zeros in between
+    rng = np.random.default_rng(5)
+    sizes = [(9000, 4096), (5000, 12000)]                 # two experts, two tensors each, different sizes
+    blobs, infos_list = [], []
+    for e, ns in enumerate(sizes):
+        for n in ns:
+            w = synth.bf16_round(rng.standard_normal(n, dtype=np.float32) * np.float32(0.02))
+            b, _ = zm.compress(w, 4096, 1024)
+            blobs.append(b)
+            infos_list.append(zm.blob_info(b[:384]))
+    infos = (zm.TensorInfo * 4)(*infos_list)
+    cfg = zm.CacheConfig(2, 2, (ctypes.c_int32 * 4)(1, 1, 1, 1), 0, 2)
+    ptrs = (ctypes.c_void_p * 4)(*[b.ctypes.data for b in blobs])
+    size = ctypes.c_size_t(0)
+    assert zm.lib().zm_cache_image_bytes(ctypes.byref(cfg), infos, ctypes.byref(size)) == zm.OK
+    up = lambda x: (x + 255) // 256 * 256
+    sm_cap = [max(up(int(infos_list[e * 2 + m].e_offset - infos_list[e * 2 + m].sm_offset)) for e in range(2)) for m in range(2)]
+    e_cap = [max(up(int(infos_list[e * 2 + m].blob_size - infos_list[e * 2 + m].e_offset)) for e in range(2)) for m in range(2)]
+    assert size.value == sum(sm_cap) + sum(e_cap)
+    for e in range(2):
+        img = np.full(size.value, 0xEE, np.uint8)
+        assert zm.lib().zm_cache_pack_expert(ctypes.byref(cfg), infos, ptrs, e, ctypes.c_void_p(img.ctypes.data), size.value) == zm.OK
+        want = np.zeros(size.value, np.uint8)
+        at = 0
+        for m in range(2):
+            i, b = infos_list[e * 2 + m], blobs[e * 2 + m]
+            want[at: at + int(i.e_offset - i.sm_offset)] = b[i.sm_offset: i.e_offset]
+            at += sm_cap[m]
+        for m in range(2):
+            i, b = infos_list[e * 2 + m], blobs[e * 2 + m]
+            want[at: at + int(i.blob_size - i.e_offset)] = b[i.e_offset: i.blob_size]
+            at += e_cap[m]
+        assert np.array_equal(img, want)
+    small = np.zeros(size.value - 1, np.uint8)
+    assert zm.lib().zm_cache_pack_expert(ctypes.byref(cfg), infos, ptrs, 0, ctypes.c_void_p(small.ctypes.data), small.size) == zm.E_SIZE
+    assert zm.lib().zm_cache_pack_expert(ctypes.byref(cfg), infos, ptrs, 2, ctypes.c_void_p(small.ctypes.data), small.size) == zm.E_ARG
