@@ -307,3 +307,10 @@ def test_packed_expert_image_layout():
     small = np.zeros(size.value - 1, np.uint8)
     assert zm.lib().zm_cache_pack_expert(ctypes.byref(cfg), infos, ptrs, 0, ctypes.c_void_p(small.ctypes.data), small.size) == zm.E_SIZE
     assert zm.lib().zm_cache_pack_expert(ctypes.byref(cfg), infos, ptrs, 2, ctypes.c_void_p(small.ctypes.data), small.size) == zm.E_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, cwd=ROOT)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
