@@ -321,7 +321,7 @@ def main() -> int:
                          "(a kernel of known traffic that scales the profiler's HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; experts are independent, so more GPUs would each decode "
+        print("bench.py: the decode path runs on one GPU; experts are independent, so more GPUs would each decode "
               "their own experts with no exchange. Run with --gpus 1.", file=sys.stderr)
         return 2
 

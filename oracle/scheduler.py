@@ -19,7 +19,7 @@ What it follows
   App. B         the charged (idle) time before a decompression on its thread; the lower bounds
                  OPT >= max(I, C/L, P, Z).
 
-Readings where the paper leaves a choice (each is listed in the design notes of the repository):
+Readings where the paper leaves a choice:
   * The I/O thread has no precedence constraints, so it runs its reads back to back: block after block,
     inside a block all E-chunk reads in task order, then all SM-chunk reads in task order.
   * A free decompression thread takes the first decompression, in (block, task position, chunk) order,

@@ -98,7 +98,7 @@ def test_plan_pools(memory, mask):
 
 
 def test_plan_feeds_the_cache_configuration():
-    """a budget of 40 % of the bf16 size of a 60-expert layer, costs in the proportions measured on the GPU machine
+    """a budget of 40 % of the bf16 size of a 60-expert layer, costs in the proportions measured on an MI355X
     (SM bytes cross the host link 2.4 times slower than E-chunks; decode is far cheaper than either)"""
     n, k = 60, 4
     f = skewed_inclusion(n, k)
