@@ -28,7 +28,7 @@ Readings where the paper leaves a choice:
   * The GPU stream takes, in the same priority order, recoveries and expert executions; an expert's
     execution has the priority of the expert's last task in the order.  The recovery has its own cost r
     (the paper's analysis has none: r = 0 gives its model).
-  * "Introduces no additional idle period": the total charged time of App. B (sum over decompressions of
+  * The insertion test of Alg. 1 (a position that adds no idle time on any thread): the total charged time of App. B (sum over decompressions of
     the idle gap before it on its thread), with the blocks built so far in front, must not grow.
   * A block is compute-dominant when, with the worker completion times sorted increasingly as
     F(1) <= ... <= F(L), F(l) - F_io >= l * rho*u/K for every l in 1..min(L, K)  (Sec. 3.3's wording;
