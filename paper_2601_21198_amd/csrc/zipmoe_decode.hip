@@ -194,7 +194,7 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         sn = rest < W ? static_cast<uint32_t>(rest) : W;
         tiles = (sn + kTile - 1) / kTile;
     }
-    const bool full = sn == kGroup * kTile;                        // the common shape: eight whole tiles
+    const bool full = sn != 0 && sn % (kGroup * kTile) == 0;       // the common shape: whole groups of eight tiles
     const uint8_t *sm_base = t.sm + v0 + lane * 8u;
     const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
 
@@ -297,16 +297,24 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         dec.lo = first.x; dec.hi = first.y;
     }
 
-    // Common case, straight-line: a full coded stream of exactly kGroup tiles.  All loads were issued
-    // above; from here on the wave only computes and stores.
+    // Common case, straight-line: a coded stream of whole groups of kGroup tiles (one group at the default
+    // stream length).  The first group's loads were issued above; from here on the wave only computes and
+    // stores, and asks for the next group's sign-mantissa bytes when a group is done.
     if (mode == ZM_MODE_CODED && full) {
+        const uint32_t groups = sn / (kGroup * kTile);
+        for (uint32_t gi = 0;;) {
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k)
-            recover_and_store<kStreaming>(out_base + k * kTile, dec.tile(len_tab, sym_tab), sm[k]);
+            for (int k = 0; k < kGroup; ++k)
+                recover_and_store<kStreaming>(out_base + (gi * kGroup + k) * kTile, dec.tile(len_tab, sym_tab), sm[k]);
+            if (++gi == groups) break;
+            // longer streams: the next eight tiles' sign-mantissa bytes
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (gi * kGroup + k) * kTile);
+        }
         return;
     }
 
-    // General case: raw chunks, short last streams, streams of more than kGroup tiles.
+    // General case: raw chunks, short last streams, streams that are not whole groups of kGroup tiles.
     for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
         if (g0) {
 #pragma unroll
