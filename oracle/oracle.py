@@ -192,6 +192,6 @@ def header(blob) -> dict:
     u32 = lambda o: int(b[o:o + 4].view("<u4")[0])
     u64 = lambda o: int(b[o:o + 8].view("<u8")[0])
     return dict(magic=u32(0), version=u32(4), n_values=u64(8), chunk_values=u32(16), stream_values=u32(20),
-                n_chunks=u32(24), L=u32(28), R=u32(32), n_present=u32(36), pad_symbol=u32(40), table_stride=u32(44),
+                n_chunks=u32(24), L=u32(28), quantum=u32(32), n_present=u32(36), pad_symbol=u32(40), table_stride=u32(44),
                 len_offset=u64(48), lut_offset=u64(56), table_offset=u64(64), sm_offset=u64(72),
                 e_offset=u64(80), blob_size=u64(88))

@@ -39,7 +39,7 @@
 /* ---- layout constants of the serialised object ------------------------- */
 
 #define ZO_MAGIC        0x454F4D5Au   /* bytes 'Z','M','O','E' */
-#define ZO_VERSION      2u
+#define ZO_VERSION      3u
 #define ZO_HEADER_BYTES 128u
 #define ZO_LANES        64u   /* per-stream lanes                              */
 #define ZO_RUN          8u    /* consecutive values one lane owns in a tile     */
@@ -53,7 +53,7 @@ enum { ZO_MODE_CODED = 0, ZO_MODE_RAW = 1 };
 /* header field offsets (bytes) */
 enum {
     H_MAGIC = 0, H_VERSION = 4, H_NVALUES = 8, H_CHUNK = 16, H_STREAM = 20,
-    H_NCHUNKS = 24, H_L = 28, H_R = 32, H_NPRESENT = 36, H_PADSYM = 40, H_TABLE_STRIDE = 44,
+    H_NCHUNKS = 24, H_L = 28, H_QUANTUM = 32, H_NPRESENT = 36, H_PADSYM = 40, H_TABLE_STRIDE = 44,
     H_LEN_OFF = 48, H_LUT_OFF = 56, H_TABLE_OFF = 64, H_SM_OFF = 72,
     H_E_OFF = 80, H_BLOB_SIZE = 88
 };
@@ -196,10 +196,6 @@ static int max_code_len(const uint8_t len[256])
     return L;
 }
 
-/* symbols per round: how many symbols every lane decodes between two refill
- * points.  A round never consumes more than 32 bits.                       */
-static uint32_t round_symbols(int L) { return L <= 8 ? 4u : 2u; }
-
 /* the symbol that fills positions past the end of a stream: the first one in
  * canonical order, whose code is all zero bits                              */
 static int pad_symbol(const uint8_t len[256])
@@ -217,152 +213,121 @@ static int pad_symbol(const uint8_t len[256])
  * symbol.
  *
  * Each lane has a bitstream of its own: the codes of its symbols one after
- * the other, the first bit of a code in the lowest free bit (LSB first),
- * packed into 32-bit little-endian words and continued with zero bits.
+ * the other, the first bit of a code first.  With m = 8*tiles symbols and T
+ * code bits, the lane's bitstream is given D = m + q*b bits in the stream,
+ * where q (the "quantum", a constant of the tensor kept in the header) and
+ * the byte b = ceil((T - m) / q) make D the smallest such number >= T; the
+ * D - T bits after the last code are zero.  (Every code has at least one
+ * bit, so T >= m; q is the smallest integer >= 1 for which b fits a byte
+ * whatever the symbols are: q >= (L - 1) * (W / 64) / 255, L the longest
+ * code of the book, W the stream length of the tensor.)
  *
- * The 64 lane bitstreams are woven into one word sequence in the order a
- * lock-step decoder needs them.  Decoding goes in rounds; in a round every
- * lane decodes R symbols (R = 4 when the longest code has at most 8 bits,
- * else 2, so that a round uses at most 32 bits).  At the start of every
- * round a lane holds words q and q+1 of its bitstream, q = (bits it has used
- * so far) / 32.  Hence:
- *   - the sequence begins with words 0 and 1 of lane 0, then of lane 1, ...
- *     (128 words);
- *   - after every round but the last, the lanes whose q went up by one take,
- *     in lane order, the next words of the sequence (each lane its own next
- *     word).
- * The sequence is padded with zero words to a multiple of 4 words.
+ * The stream is
+ *   bytes 0..63   b of lane 0, lane 1, ..., lane 63
+ *   then          the 64 lane bitstreams one right after the other, lane 0
+ *                 first, with no gap: lane j starts at bit D_0 + .. + D_(j-1).
+ *                 Bit k of this payload is bit (k mod 32) of its 32-bit
+ *                 little-endian word k / 32, i.e. bit (k mod 8) of byte k / 8.
+ *   then          zero bits up to a multiple of 16 bytes.
+ * A decoder finds every lane's first bit with a prefix sum over the 64 bytes
+ * and then reads each lane's bits independently of the others.
  */
 
-/* worst-case number of 32-bit words of one coded stream */
-static size_t stream_words_bound(uint32_t stream_values)
+/* the quantum q of a tensor whose longest code has L bits and whose streams
+ * hold W values                                                            */
+static uint32_t lane_quantum(int L, uint32_t W)
+{
+    uint32_t span = (uint32_t)(L - 1) * (W / ZO_LANES);
+    uint32_t q = (span + 254) / 255;
+    return q ? q : 1;
+}
+
+/* worst-case number of bytes of one coded stream */
+static size_t stream_bytes_bound(uint32_t stream_values)
 {
     size_t tiles = (stream_values + ZO_TILE - 1) / ZO_TILE;
-    size_t bits_per_lane = tiles * ZO_RUN * ZO_MAX_LEN;
-    return ZO_LANES * (2 + (bits_per_lane + 31) / 32) + 4;
+    size_t bits = (size_t)ZO_LANES * (tiles * ZO_RUN * ZO_MAX_LEN + 255);   /* code bits + rounding to the quantum */
+    return round_up(ZO_LANES + (bits + 7) / 8, 16);
 }
 
-/* Encodes exponents e[0..n) (n <= stream_values) into out[]; returns words
- * written (a multiple of 4).                                               */
+static void put_bit(uint8_t *payload, uint64_t k, uint32_t bit)
+{
+    payload[k / 8] |= (uint8_t)(bit << (k % 8));
+}
+
+static uint32_t get_bit(const uint8_t *payload, uint64_t k)
+{
+    return (payload[k / 8] >> (k % 8)) & 1u;
+}
+
+/* Encodes exponents e[0..n) (n <= stream_values) into out[], which must be
+ * zero on entry; returns bytes written (a multiple of 16).                 */
 static size_t encode_stream(const uint8_t *e, uint32_t n, const uint8_t len[256],
-                            const uint16_t code[256], int L, int pad, uint32_t *out)
+                            const uint16_t code[256], uint32_t q, int pad, uint8_t *out)
 {
-    const uint32_t R = round_symbols(L);
     const uint32_t tiles = (n + ZO_TILE - 1) / ZO_TILE;
-    const uint32_t nsym = tiles * ZO_RUN;        /* symbols per lane */
-    const uint32_t rounds = nsym / R;
-    const size_t lane_words = 2 + ((size_t)nsym * ZO_MAX_LEN + 31) / 32 + 1;
-
-    /* 1. every lane's own bitstream, as words, plus the bit position after
-     *    each of its symbols                                                */
-    uint32_t *words = (uint32_t *)calloc(ZO_LANES * lane_words, sizeof(uint32_t));
-    uint32_t *used_after = (uint32_t *)calloc((size_t)ZO_LANES * (nsym + 1), sizeof(uint32_t));
+    const uint32_t m = tiles * ZO_RUN;           /* symbols per lane */
+    uint8_t *payload = out + ZO_LANES;
+    uint64_t at = 0;                             /* payload bit where the current lane starts */
     for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
-        uint32_t pos = 0;
-        for (uint32_t j = 0; j < nsym; j++) {
-            uint32_t t = j / ZO_RUN, i = j % ZO_RUN;
-            uint32_t idx = t * ZO_TILE + lane * ZO_RUN + i;
+        uint64_t k = at;
+        for (uint32_t j = 0; j < m; j++) {
+            uint32_t idx = (j / ZO_RUN) * ZO_TILE + lane * ZO_RUN + (j % ZO_RUN);
             int s = idx < n ? e[idx] : pad;
-            for (int b = len[s] - 1; b >= 0; b--) {       /* first wire bit = top bit of the code */
-                uint32_t bit = (code[s] >> b) & 1u;
-                words[lane * lane_words + pos / 32] |= bit << (pos % 32);
-                pos++;
-            }
-            used_after[(size_t)lane * (nsym + 1) + j + 1] = pos;
+            for (int b = len[s] - 1; b >= 0; b--)            /* first wire bit = top bit of the code */
+                put_bit(payload, k++, (code[s] >> b) & 1u);
         }
+        uint32_t T = (uint32_t)(k - at);
+        uint32_t units = (T - m + q - 1) / q;                /* at most 255 by the choice of q */
+        out[lane] = (uint8_t)units;
+        at += m + (uint64_t)q * units;
     }
-    /* 2. weave */
-    size_t w = 0;
-    uint32_t have[ZO_LANES];
-    for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
-        out[w++] = words[lane * lane_words + 0];
-        out[w++] = words[lane * lane_words + 1];
-        have[lane] = 2;
-    }
-    for (uint32_t r = 0; r + 1 < rounds; r++) {
-        for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
-            uint32_t used = used_after[(size_t)lane * (nsym + 1) + (r + 1) * R];
-            uint32_t q = used / 32;
-            while (have[lane] < q + 2) {               /* at most once: a round uses <= 32 bits */
-                out[w++] = words[lane * lane_words + have[lane]];
-                have[lane]++;
-            }
-        }
-    }
-    while (w % 4) out[w++] = 0;
-    free(words); free(used_after);
-    return w;
+    return round_up(ZO_LANES + (at + 7) / 8, 16);
 }
 
-/* read bit number pos of a lane's bitstream held as a word list */
-static int lane_bit(const uint32_t *lane_words, uint32_t pos)
-{
-    return (int)((lane_words[pos / 32] >> (pos % 32)) & 1u);
-}
-
-/* Decodes one stream.  words/n_words: the woven sequence as stored (padding
- * included).  Writes n exponent bytes.  Checks everything it can: that every
- * bit it reads lies in a word the lane holds, that every code is a code of
- * the book, that pad positions hold the pad symbol, and that the sequence
- * has exactly the words the schedule asks for plus zero padding up to a
- * multiple of 4.                                                           */
-static int decode_stream(const uint32_t *words, size_t n_words, uint32_t n,
+/* Decodes one stream of n_bytes bytes as stored.  Writes n exponent bytes.
+ * Checks everything it can: that every bit it reads lies inside the lane's
+ * own D bits, that every code is a code of the book, that pad positions hold
+ * the pad symbol, that the lane's byte is the smallest that fits its codes,
+ * that the bits between a lane's last code and the next lane are zero, and
+ * that the stream ends, after zero bits only, at the first multiple of 16
+ * bytes.                                                                   */
+static int decode_stream(const uint8_t *stream, size_t n_bytes, uint32_t n,
                          const uint8_t len[256], const uint16_t code[256],
-                         int L, int pad, uint8_t *e)
+                         int L, uint32_t q, int pad, uint8_t *e)
 {
-    const uint32_t R = round_symbols(L);
     const uint32_t tiles = (n + ZO_TILE - 1) / ZO_TILE;
-    const uint32_t nsym = tiles * ZO_RUN;
-    const uint32_t rounds = nsym / R;
-    const size_t cap = 2 + ((size_t)nsym * ZO_MAX_LEN + 31) / 32 + 1;
-    int rc = ZO_OK;
-
-    if (n_words < 2 * ZO_LANES) return ZO_E_FORMAT;
-    uint32_t *mine = (uint32_t *)calloc(ZO_LANES * cap, sizeof(uint32_t));   /* words each lane holds */
-    uint32_t have[ZO_LANES], used[ZO_LANES];
-    size_t w = 0;
+    const uint32_t m = tiles * ZO_RUN;
+    if (n_bytes < ZO_LANES || n_bytes % 16) return ZO_E_FORMAT;
+    const uint8_t *payload = stream + ZO_LANES;
+    const uint64_t payload_bits = (uint64_t)(n_bytes - ZO_LANES) * 8;
+    uint64_t at = 0;
     for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
-        mine[lane * cap + 0] = words[w++];
-        mine[lane * cap + 1] = words[w++];
-        have[lane] = 2; used[lane] = 0;
-    }
-    for (uint32_t r = 0; r < rounds && rc == ZO_OK; r++) {
-        for (uint32_t lane = 0; lane < ZO_LANES && rc == ZO_OK; lane++) {
-            for (uint32_t k = 0; k < R; k++) {
-                /* walk the code one bit at a time until it equals a code of the book */
-                uint32_t acc = 0; int l = 0, found = -1;
-                while (found < 0 && l < L) {
-                    if (used[lane] / 32 >= have[lane]) { rc = ZO_E_FORMAT; break; }
-                    acc = (acc << 1) | (uint32_t)lane_bit(mine + lane * cap, used[lane]);
-                    used[lane]++; l++;
-                    for (int s = 0; s < 256; s++)
-                        if (len[s] == l && code[s] == acc) { found = s; break; }
-                }
-                if (rc != ZO_OK) break;
-                if (found < 0) { rc = ZO_E_FORMAT; break; }
-                uint32_t j = r * R + k;
-                uint32_t idx = (j / ZO_RUN) * ZO_TILE + lane * ZO_RUN + (j % ZO_RUN);
-                if (idx < n) e[idx] = (uint8_t)found;
-                else if (found != pad) { rc = ZO_E_FORMAT; break; }
+        const uint64_t D = m + (uint64_t)q * stream[lane];
+        if (at + D > payload_bits) return ZO_E_FORMAT;
+        uint64_t k = at;
+        for (uint32_t j = 0; j < m; j++) {
+            /* walk the code one bit at a time until it equals a code of the book */
+            uint32_t acc = 0; int l = 0, found = -1;
+            while (found < 0 && l < L) {
+                if (k >= at + D) return ZO_E_FORMAT;
+                acc = (acc << 1) | get_bit(payload, k);
+                k++; l++;
+                for (int s = 0; s < 256; s++)
+                    if (len[s] == l && code[s] == acc) { found = s; break; }
             }
+            if (found < 0) return ZO_E_FORMAT;
+            uint32_t idx = (j / ZO_RUN) * ZO_TILE + lane * ZO_RUN + (j % ZO_RUN);
+            if (idx < n) e[idx] = (uint8_t)found;
+            else if (found != pad) return ZO_E_FORMAT;
         }
-        if (rc != ZO_OK || r + 1 == rounds) break;
-        for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
-            uint32_t q = used[lane] / 32;
-            while (have[lane] < q + 2) {
-                if (w >= n_words) { rc = ZO_E_FORMAT; break; }
-                mine[lane * cap + have[lane]] = words[w++];
-                have[lane]++;
-            }
-            if (rc != ZO_OK) break;
-        }
+        if (at + D - k >= q) return ZO_E_FORMAT;             /* a smaller byte would have done */
+        for (; k < at + D; k++) if (get_bit(payload, k)) return ZO_E_FORMAT;
+        at += D;
     }
-    if (rc == ZO_OK) {
-        if (n_words - w >= 4 || n_words % 4) rc = ZO_E_FORMAT;
-        for (size_t j = w; j < n_words && rc == ZO_OK; j++) if (words[j] != 0) rc = ZO_E_FORMAT;
-    }
-    free(mine);
-    return rc;
+    if (n_bytes != round_up(ZO_LANES + (at + 7) / 8, 16)) return ZO_E_FORMAT;
+    for (uint64_t k = at; k < payload_bits; k++) if (get_bit(payload, k)) return ZO_E_FORMAT;
+    return ZO_OK;
 }
 
 /* ---- the serialised tensor --------------------------------------------- */
@@ -460,7 +425,9 @@ int zo_encode(const uint16_t *w, size_t n, uint32_t C, uint32_t W,
     }
     memcpy(blob + sm_off, sm, n);
 
-    uint32_t *tmp = (uint32_t *)malloc(stream_words_bound(W) * sizeof(uint32_t));
+    const uint32_t q = lane_quantum(L, W);
+    const size_t tmp_bytes = stream_bytes_bound(W);
+    uint8_t *tmp = (uint8_t *)malloc(tmp_bytes);
     uint64_t pos = e_off;
     for (size_t c = 0; c < K; c++) {
         uint32_t cn = (uint32_t)((n - c * C) < C ? (n - c * C) : C);
@@ -474,11 +441,12 @@ int zo_encode(const uint16_t *w, size_t n, uint32_t C, uint32_t W,
         memset(entry, 0, stride);
         for (uint32_t s = 0; s < S && fits; s++) {
             uint32_t sn = (cn - s * W) < W ? (cn - s * W) : W;
-            size_t nw = encode_stream(e + c * C + (size_t)s * W, sn, len, code, L, pad, tmp);
+            memset(tmp, 0, tmp_bytes);
+            size_t nb = encode_stream(e + c * C + (size_t)s * W, sn, len, code, q, pad, tmp);
             put32(entry + 8 + 4 * s, (uint32_t)at);
-            if (at + 4 * nw >= raw_bytes) { fits = 0; break; }
-            for (size_t j = 0; j < nw; j++) put32(base + at + 4 * j, tmp[j]);
-            at += 4 * nw;
+            if (at + nb >= raw_bytes) { fits = 0; break; }
+            memcpy(base + at, tmp, nb);
+            at += nb;
         }
         if (fits && at < raw_bytes) {
             put32(entry + 8 + 4 * S, (uint32_t)at);
@@ -500,7 +468,7 @@ int zo_encode(const uint16_t *w, size_t n, uint32_t C, uint32_t W,
     put32(blob + H_MAGIC, ZO_MAGIC); put32(blob + H_VERSION, ZO_VERSION);
     put64(blob + H_NVALUES, n); put32(blob + H_CHUNK, C); put32(blob + H_STREAM, W);
     put32(blob + H_NCHUNKS, (uint32_t)K); put32(blob + H_L, (uint32_t)L);
-    put32(blob + H_R, round_symbols(L)); put32(blob + H_NPRESENT, (uint32_t)n_present);
+    put32(blob + H_QUANTUM, q); put32(blob + H_NPRESENT, (uint32_t)n_present);
     put32(blob + H_PADSYM, (uint32_t)pad); put32(blob + H_TABLE_STRIDE, (uint32_t)stride);
     put64(blob + H_LEN_OFF, len_off); put64(blob + H_LUT_OFF, lut_off);
     put64(blob + H_TABLE_OFF, table_off); put64(blob + H_SM_OFF, sm_off);
@@ -546,7 +514,8 @@ int zo_decode_chunks(const uint8_t *blob, size_t size, size_t c0, size_t c1, uin
     const uint8_t *len = blob + len_off;
     if (zo_kraft_units(len) > (1u << ZO_MAX_LEN)) return ZO_E_FORMAT;
     if (max_code_len(len) != L) return ZO_E_FORMAT;
-    if (get32(blob + H_R) != round_symbols(L)) return ZO_E_FORMAT;
+    const uint32_t q = lane_quantum(L, W);
+    if (get32(blob + H_QUANTUM) != q) return ZO_E_FORMAT;
     uint16_t code[256];
     int n_present = zo_canonical(len, code);
     int pad = pad_symbol(len);
@@ -554,7 +523,6 @@ int zo_decode_chunks(const uint8_t *blob, size_t size, size_t c0, size_t c1, uin
 
     const uint8_t *sm = blob + sm_off;
     uint8_t *e = (uint8_t *)malloc(C);
-    uint32_t *wbuf = (uint32_t *)malloc(stream_words_bound(W) * sizeof(uint32_t));
     int rc = ZO_OK;
     for (uint64_t c = c0; c < c1 && rc == ZO_OK; c++) {
         const uint8_t *entry = blob + table_off + stride * c;
@@ -578,17 +546,14 @@ int zo_decode_chunks(const uint8_t *blob, size_t size, size_t c0, size_t c1, uin
             for (uint32_t s = 0; s < S && rc == ZO_OK; s++) {
                 uint32_t o0 = get32(entry + 8 + 4 * s), o1 = get32(entry + 8 + 4 * (s + 1));
                 if (o0 % 16 || o1 % 16 || o1 < o0 || o1 > end - at) { rc = ZO_E_FORMAT; break; }
-                size_t nw = (o1 - o0) / 4;
-                if (nw > stream_words_bound(W)) { rc = ZO_E_FORMAT; break; }
-                for (size_t j = 0; j < nw; j++) wbuf[j] = get32(base + o0 + 4 * j);
                 uint32_t sn = (cn - s * W) < W ? (cn - s * W) : W;
-                rc = decode_stream(wbuf, nw, sn, len, code, L, pad, e + (size_t)s * W);
+                rc = decode_stream(base + o0, o1 - o0, sn, len, code, L, q, pad, e + (size_t)s * W);
             }
         } else rc = ZO_E_FORMAT;
         if (rc == ZO_OK) zo_merge(e, sm + c * C, cn, out + c * C);
     }
     if (rc == ZO_OK && c1 == K && get64(blob + table_off + stride * K) > total) rc = ZO_E_FORMAT;
-    free(e); free(wbuf);
+    free(e);
     return rc;
 }
 
