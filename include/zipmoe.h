@@ -46,13 +46,18 @@
  *              chunk c covers values [c*chunk_values, (c+1)*chunk_values).
  *              mode 1 (raw): the exponent bytes.  mode 0 (coded): the chunk's
  *              streams one after the other.
- *              A stream covers stream_values consecutive values and weaves 64
- *              per-lane bitstreams into one sequence of 32-bit words in the
- *              order a 64-lane lock-step decoder consumes them: in every tile
- *              of 512 values lane j owns values 8j..8j+7; each lane starts
- *              with two words and takes one more word whenever, at the end of
- *              a round of R symbols (R = 4 for L <= 8, else 2), its bit count
- *              has crossed a 32-bit boundary.
+ *              A stream covers stream_values consecutive values, cut into
+ *              tiles of 512; in every tile lane j of 64 owns values 8j..8j+7.
+ *              A lane's bitstream is the codes of its m symbols (8 per tile,
+ *              tile after tile; positions past the stream's end hold the
+ *              first symbol in canonical order), first code bit first,
+ *              followed by zero bits up to D = m + q*b bits, b the smallest
+ *              byte that fits.  The stream is the 64 bytes b (lane 0 first),
+ *              then the 64 bitstreams back to back with no gap (payload bit k
+ *              is bit k%32 of the little-endian 32-bit word k/32), then zero
+ *              bits to a multiple of 16 bytes.  A prefix sum over the 64 bytes
+ *              gives every lane's first bit.  q, the header's lane_quantum, is
+ *              the smallest integer >= 1 with (L-1)*(stream_values/64) <= 255*q.
  */
 #ifndef ZIPMOE_H
 #define ZIPMOE_H
@@ -89,7 +94,7 @@ typedef struct zm_tensor_info {
     uint32_t stream_values;  /* values per stream inside a chunk                  */
     uint32_t n_chunks;
     uint32_t max_len;        /* L, longest code length in use (>= 1)              */
-    uint32_t round_symbols;  /* R                                                 */
+    uint32_t lane_quantum;   /* q: unit, in bits, of the per-lane length bytes    */
     uint32_t n_present;      /* exponent values that occur                        */
     uint32_t table_stride;   /* bytes of one chunk-table entry                    */
     uint32_t reserved;

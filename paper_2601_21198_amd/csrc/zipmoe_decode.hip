@@ -14,18 +14,18 @@
 //           both contiguous across the wave (512 B and 1 KiB per instruction)
 //
 // Per wave
-//   1. one read of the chunk's table entry locates the stream; its words are
-//      requested with 128-bit loads (a4) -- first, because decoding can not start
-//      without them -- and go to LDS;
+//   1. one read of the chunk's table entry locates the stream; its bytes (64 lane-length bytes, then the 64
+//      lane bitstreams back to back) are requested with 128-bit loads (a4) -- first, because decoding can not
+//      start without them -- and go to LDS;
 //   2. the sign-mantissa bytes of the stream's first eight tiles are requested;
 //   3. the decode table goes to LDS (a3) as two byte tables (code length, symbol)
 //      at fixed LDS addresses, replicated to the full index width;
-//   4. lock-step decode (a5): every lane keeps two words (lo, hi) of its own
-//      bitstream and a bit position; per round it extracts a 32-bit window with
-//      one funnel shift and decodes R symbols by table lookup;
-//   5. after a round the lanes whose position passed 32 bits take the next
-//      words of the stream: a ballot marks them, a prefix count over the ballot
-//      (mbcnt) gives each its word (a6);
+//   4. a wavefront prefix sum over the 64 lane-length bytes gives every lane the first bit of its own
+//      bitstream (a6): what varies from lane to lane is where its input lies, its output positions are fixed;
+//   5. lock-step decode (a5): every lane keeps two words (lo, hi) of its bitstream, a bit position and the
+//      index of its next word; per round it extracts a 32-bit window with one funnel shift and decodes R
+//      symbols by table lookup; the next word is requested at the start of the round, so that a lane that
+//      crosses a word boundary finds it there;
 //   6. the eight decoded exponent bytes are merged with the sign-mantissa bytes
 //      by byte-parallel bit operations and stored (a8).
 #include <hip/hip_runtime.h>
@@ -54,22 +54,33 @@ struct Task {
     uint32_t stream_values;
     uint32_t streams_per_chunk;
     uint32_t n_streams;
-    uint32_t max_len;
+    uint32_t code;            // longest code length | lane quantum << 8
 };
 
 struct Launch {
     uint32_t n_tasks;
     uint32_t stream_cap_words;   // LDS words reserved per wave for its stream
-    uint32_t pad[2];
+    uint32_t streams_per_wave;   // consecutive streams of a tensor that one wave decodes
+    uint32_t pad;
     Task task[kMaxTasks];        // blockIdx.y selects the task
 };
 static_assert(sizeof(Launch) <= 4096, "kernel arguments must stay under 4 KiB");
 
-// base + number of set bits of `mask` below this lane (the exclusive prefix count of a ballot)
-__device__ __forceinline__ uint32_t lanes_below(uint64_t mask, uint32_t base)
+constexpr uint32_t kLaneBytes = 64;   // a stream opens with one length byte per lane
+
+// Exclusive prefix sum of x over the 64 lanes of the wave (a6), by data-parallel primitives: an inclusive
+// scan inside each row of 16 lanes (shifts by 1, 2, 4, 8), then lane 15 of row 0 and 2 is added to the next
+// row, then lane 31 to rows 2 and 3.  Lanes with no source keep the `old` operand, zero.
+__device__ __forceinline__ uint32_t wave_exclusive_sum(uint32_t x)
 {
-    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
-                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), base));
+    uint32_t v = x;
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v - x;
 }
 
 // Sec. 3.3 recovery of four values at once: e4 and sm4 hold four exponent bytes
@@ -113,14 +124,24 @@ struct Code {
     static constexpr uint32_t kEntries = 1u << kIndexBits;
 };
 
-// Lock-step decoder state of one lane (a5, a6).  len_tab / sym_tab are the workgroup's byte tables.
+// Lock-step decoder state of one lane (a5).  len_tab / sym_tab are the workgroup's byte tables.
 template <int R>
 struct Decoder {
-    const uint32_t *words;
-    uint32_t last_word;
+    const uint32_t *words;        // the stream as staged in LDS (length bytes included)
+    uint32_t last_word;           // highest index a read may use
     uint32_t lo = 0, hi = 0;      // words q and q+1 of this lane's bitstream
     uint32_t pos = 0;             // bits of lo already used (< 32 at the start of a round)
-    uint32_t next = 128;          // next unread word of the stream (uniform over the wave)
+    uint32_t next = 0;            // index of word q+2
+
+    // first_bit: where this lane's bitstream starts, counted from the first payload bit
+    __device__ __forceinline__ void start(uint32_t first_bit)
+    {
+        const uint32_t q = kLaneBytes / 4 + (first_bit >> 5);
+        pos = first_bit & 31u;
+        lo = words[min(q, last_word)];
+        hi = words[min(q + 1u, last_word)];
+        next = q + 2u;
+    }
 
     // Decodes this lane's eight exponent bytes of one tile.
     __device__ __forceinline__ uint2 tile(const uint8_t *len_tab, const uint8_t *sym_tab)
@@ -129,6 +150,8 @@ struct Decoder {
         uint32_t e[2] = {0u, 0u};
 #pragma unroll
         for (int r = 0; r < 8 / R; ++r) {
+            // the word this lane takes if the round crosses a word boundary: asked for now, used after the round
+            const uint32_t fresh = words[min(next, last_word)];
             // R symbols out of one 32-bit window; `used` is the bit offset of the next code in it
             const uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
             uint32_t used = 0;
@@ -148,30 +171,26 @@ struct Decoder {
                 const uint32_t s01 = __builtin_amdgcn_perm(s[1], s[0], 0x0c0c0400u);
                 e[r >> 1] = (r & 1) ? __builtin_amdgcn_perm(s01, e[r >> 1], 0x05040100u) : s01;
             }
-            // a6: lanes that crossed a word boundary take the stream's next words, in lane order: the
-            // ballot's prefix count is each taker's offset.  Written without branches (every lane reads
-            // a word, only the takers keep it) so that the whole tile is one basic block.  After the
-            // stream's last round the word read here is never used.
+            // written without branches so that the whole tile is one basic block
             const bool take = pos >= 32u;
-            const uint64_t takers = __ballot(take);
-            const uint32_t fresh = words[min(lanes_below(takers, next), last_word)];
             lo = take ? hi : lo;
             hi = take ? fresh : hi;
+            next += take ? 1u : 0u;
             pos &= 31u;
-            next += static_cast<uint32_t>(__builtin_popcountll(takers));
         }
         return make_uint2(e[0], e[1]);
     }
 };
 
-// R: symbols per round; kWaves: waves (streams) per workgroup; kStreaming: non-temporal stores
-template <int R, int kWaves, bool kStreaming>
+// R: symbols per round; kWaves: waves per workgroup; kStreaming: non-temporal stores; kLoop: a wave decodes
+// P.streams_per_wave streams, else one
+template <int R, int kWaves, bool kStreaming, bool kLoop>
 __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
 {
     // Byte tables of the workgroup's tensor, at fixed LDS addresses so that a lookup is one LDS read with
     // an immediate offset.  The lookups of a wave hit random words of a 64-word table and do collide on
-    // banks (the counters show conflicts in 45 % of the LDS-active cycles), but waves spend about 1 % of
-    // their cycles waiting for LDS: confining the lookups to 32- or 16-word tables changed nothing.
+    // banks, but waves spend about 1 % of their cycles waiting for LDS: confining the lookups to 32- or
+    // 16-word tables changed nothing.
     __shared__ __align__(16) uint8_t len_tab[Code<R>::kEntries];
     __shared__ __align__(16) uint8_t sym_tab[Code<R>::kEntries];
     extern __shared__ __align__(16) uint32_t stream_lds[];
@@ -182,160 +201,170 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     // grid: x = workgroup inside the tensor, y = tensor.  The task is copied with one batch of scalar loads.
     const Task t = P.task[blockIdx.y];
     uint32_t *words = stream_lds + wave * P.stream_cap_words;
-
-    const uint32_t g = blockIdx.x * kWaves + wave;
-    bool active = g < t.n_streams;
     const uint32_t W = t.stream_values;
-    const uint64_t v0 = static_cast<uint64_t>(g) * W;              // first value of the stream in the tensor
-    uint32_t sn = 0, mode = ZM_MODE_RAW, tiles = 0;
-    const uint8_t *raw = nullptr;
-    if (active) {
-        const uint64_t rest = t.n_values - v0;
-        sn = rest < W ? static_cast<uint32_t>(rest) : W;
-        tiles = (sn + kTile - 1) / kTile;
-    }
-    const bool full = sn != 0 && sn % (kGroup * kTile) == 0;       // the common shape: whole groups of eight tiles
-    const uint8_t *sm_base = t.sm + v0 + lane * 8u;
-    const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
+    const uint32_t max_len = t.code & 0xffu, quantum = t.code >> 8;
+    const uint32_t stride = (8u + 4u * (t.streams_per_chunk + 1u) + 7u) & ~7u;     // bytes of a chunk-table entry
 
-    uint4 held_a = make_uint4(0u, 0u, 0u, 0u), held_b = held_a;   // first 2 KiB of the stream
-    uint32_t n_held = 0;
-    if (active) {
-        const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
-        // one read of the chunk's table entry gives the chunk's place and mode and this stream's extent
-        const uint32_t stride = (8u + 4u * (t.streams_per_chunk + 1u) + 7u) & ~7u;
-        const uint8_t *entry = reinterpret_cast<const uint8_t *>(t.table) + static_cast<uint64_t>(c) * stride;
-        const uint64_t ent = *reinterpret_cast<const uint64_t *>(entry);
-        const uint32_t o0 = reinterpret_cast<const uint32_t *>(entry + 8)[s];
-        const uint32_t o1 = reinterpret_cast<const uint32_t *>(entry + 8)[s + 1];
-        const uint64_t at = (ent & ~15ull) - t.e_offset;            // offset inside the E-chunk region
-        mode = static_cast<uint32_t>(ent & 15ull);
-        if ((ent & ~15ull) < t.e_offset) {
-            active = false;
-        } else if (mode == ZM_MODE_CODED) {
-            // a4: the stream's words, 128 bits per lane per load.  They are requested before the (larger)
-            // sign-mantissa bytes because decoding can not start without them; the first 2 KiB (two
-            // vectors per lane, more than a typical stream) wait in registers until the other requests
-            // are out, longer streams are copied here.
-            if (o1 < o0 || at + o1 > t.e_size) {
+    // every wave decodes streams_per_wave consecutive streams of its tensor, one after the other
+    const uint32_t per_wave = kLoop ? P.streams_per_wave : 1u;
+    const uint32_t g_first = (blockIdx.x * kWaves + wave) * per_wave;
+    for (uint32_t gi = 0; gi < per_wave; ++gi) {
+        const uint32_t g = g_first + gi;
+        bool active = g < t.n_streams;
+        const uint64_t v0 = static_cast<uint64_t>(g) * W;              // first value of the stream in the tensor
+        uint32_t sn = 0, mode = ZM_MODE_RAW, tiles = 0;
+        const uint8_t *raw = nullptr;
+        if (active) {
+            const uint64_t rest = t.n_values - v0;
+            sn = rest < W ? static_cast<uint32_t>(rest) : W;
+            tiles = (sn + kTile - 1) / kTile;
+        }
+        const bool full = sn != 0 && sn % (kGroup * kTile) == 0;       // the common shape: whole groups of eight tiles
+        const uint8_t *sm_base = t.sm + v0 + lane * 8u;
+        const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
+
+        uint4 held_a = make_uint4(0u, 0u, 0u, 0u), held_b = held_a;   // first 2 KiB of the stream
+        uint32_t n_held = 0;
+        if (active) {
+            const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
+            // one read of the chunk's table entry gives the chunk's place and mode and this stream's extent
+            const uint8_t *entry = reinterpret_cast<const uint8_t *>(t.table) + static_cast<uint64_t>(c) * stride;
+            const uint64_t ent = *reinterpret_cast<const uint64_t *>(entry);
+            const uint32_t o0 = reinterpret_cast<const uint32_t *>(entry + 8)[s];
+            const uint32_t o1 = reinterpret_cast<const uint32_t *>(entry + 8)[s + 1];
+            const uint64_t at = (ent & ~15ull) - t.e_offset;            // offset inside the E-chunk region
+            mode = static_cast<uint32_t>(ent & 15ull);
+            if ((ent & ~15ull) < t.e_offset) {
                 active = false;
+            } else if (mode == ZM_MODE_CODED) {
+                // a4: the stream's bytes, 128 bits per lane per load.  They are requested before the (larger)
+                // sign-mantissa bytes because decoding can not start without them; the first 2 KiB (two
+                // vectors per lane, more than a typical stream) wait in registers until the other requests
+                // are out, longer streams are copied here.
+                if (o1 < o0 + kLaneBytes || at + o1 > t.e_size) {
+                    active = false;
+                } else {
+                    const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
+                    const uint4 *src = reinterpret_cast<const uint4 *>(t.echunks + at + o0);
+                    uint4 *dst = reinterpret_cast<uint4 *>(words);
+                    n_held = min(nvec, 128u);
+                    if (lane < n_held) held_a = src[lane];
+                    if (lane + 64 < n_held) held_b = src[lane + 64];
+                    for (uint32_t i = 128 + lane; i < nvec; i += 64) dst[i] = src[i];
+                }
             } else {
-                const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
-                const uint4 *src = reinterpret_cast<const uint4 *>(t.echunks + at + o0);
-                uint4 *dst = reinterpret_cast<uint4 *>(words);
-                n_held = min(nvec, 128u);
-                if (lane < n_held) held_a = src[lane];
-                if (lane + 64 < n_held) held_b = src[lane + 64];
-                for (uint32_t i = 128 + lane; i < nvec; i += 64) dst[i] = src[i];
-            }
-        } else {
-            raw = t.echunks + at + static_cast<uint64_t>(s) * W;
-            if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.e_size) active = false;
-        }
-    }
-    // Next in the request order: the sign-mantissa bytes of the first kGroup tiles.  They stay in flight
-    // while the stream is staged and decoding starts.
-    uint2 sm[kGroup];
-    if (full) {
-#pragma unroll
-        for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
-    } else {
-#pragma unroll
-        for (int k = 0; k < kGroup; ++k) {
-            sm[k] = make_uint2(0u, 0u);
-            if (static_cast<uint32_t>(k) < tiles && mine - static_cast<int32_t>(k * kTile) > 0)
-                sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
-        }
-    }
-
-    // a3: decode table -> LDS, split into a length table and a symbol table and replicated over the
-    // index bits above the longest code.  Every wave of the workgroup writes the same bytes (LDS word
-    // writes are atomic), so a wave may read as soon as its own writes are done: no workgroup barrier.
-    {
-        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.lut);
-        const uint32_t mask = (1u << t.max_len) - 1u;
-        if (R == 4) {
-            // 256 entries, four per lane, all loads issued before the first is used
-            const uint32_t i = 4u * lane;
-            const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
-            const uint32_t ab = a | (b << 16), cd = c | (d << 16);
-            reinterpret_cast<uint32_t *>(sym_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x06040200u);
-            reinterpret_cast<uint32_t *>(len_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x07050301u);
-        } else {
-            // 4096 entries; R = 2 implies max_len >= 9, so any 16 consecutive entries stay consecutive under the mask
-            for (uint32_t i = 16u * lane; i < Code<R>::kEntries; i += 16u * 64u) {
-                const uint4 *v = reinterpret_cast<const uint4 *>(src + (i & mask));
-                const uint4 x = v[0], y = v[1];
-                uint4 sy, le;
-                sy.x = __builtin_amdgcn_perm(x.y, x.x, 0x06040200u); le.x = __builtin_amdgcn_perm(x.y, x.x, 0x07050301u);
-                sy.y = __builtin_amdgcn_perm(x.w, x.z, 0x06040200u); le.y = __builtin_amdgcn_perm(x.w, x.z, 0x07050301u);
-                sy.z = __builtin_amdgcn_perm(y.y, y.x, 0x06040200u); le.z = __builtin_amdgcn_perm(y.y, y.x, 0x07050301u);
-                sy.w = __builtin_amdgcn_perm(y.w, y.z, 0x06040200u); le.w = __builtin_amdgcn_perm(y.w, y.z, 0x07050301u);
-                *reinterpret_cast<uint4 *>(sym_tab + i) = sy;
-                *reinterpret_cast<uint4 *>(len_tab + i) = le;
+                raw = t.echunks + at + static_cast<uint64_t>(s) * W;
+                if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.e_size) active = false;
             }
         }
-    }
-
-    if (n_held) {
-        uint4 *dst = reinterpret_cast<uint4 *>(words);
-        if (lane < n_held) dst[lane] = held_a;
-        if (lane + 64 < n_held) dst[lane + 64] = held_b;
-    }
-    // LDS written by some lanes of this wave is read by others: order the LDS accesses only
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-    if (!active) return;
-
-    uint16_t *out_base = t.out + v0 + lane * 8u;
-
-    Decoder<R> dec;
-    dec.words = words; dec.last_word = P.stream_cap_words - 1u;
-    if (mode == ZM_MODE_CODED) {
-        const uint2 first = reinterpret_cast<const uint2 *>(words)[lane];
-        dec.lo = first.x; dec.hi = first.y;
-    }
-
-    // Common case, straight-line: a coded stream of whole groups of kGroup tiles (one group at the default
-    // stream length).  The first group's loads were issued above; from here on the wave only computes and
-    // stores, and asks for the next group's sign-mantissa bytes when a group is done.
-    if (mode == ZM_MODE_CODED && full) {
-        const uint32_t groups = sn / (kGroup * kTile);
-        for (uint32_t gi = 0;;) {
+        // Next in the request order: the sign-mantissa bytes of the first kGroup tiles.  They stay in flight
+        // while the stream is staged and decoding starts.
+        uint2 sm[kGroup];
+        if (full) {
 #pragma unroll
-            for (int k = 0; k < kGroup; ++k)
-                recover_and_store<kStreaming>(out_base + (gi * kGroup + k) * kTile, dec.tile(len_tab, sym_tab), sm[k]);
-            if (++gi == groups) break;
-            // longer streams: the next eight tiles' sign-mantissa bytes
-#pragma unroll
-            for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (gi * kGroup + k) * kTile);
-        }
-        return;
-    }
-
-    // General case: raw chunks, short last streams, streams that are not whole groups of kGroup tiles.
-    for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
-        if (g0) {
+            for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
+        } else {
 #pragma unroll
             for (int k = 0; k < kGroup; ++k) {
                 sm[k] = make_uint2(0u, 0u);
-                if (g0 + k < tiles && mine - static_cast<int32_t>((g0 + k) * kTile) > 0)
-                    sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (g0 + k) * kTile);
+                if (static_cast<uint32_t>(k) < tiles && mine - static_cast<int32_t>(k * kTile) > 0)
+                    sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
             }
         }
+
+        // a3 (first stream only): decode table -> LDS, split into a length table and a symbol table and
+        // replicated over the index bits above the longest code.  Every wave of the workgroup writes the same
+        // bytes (LDS word writes are atomic), so a wave may read as soon as its own writes are done: no
+        // workgroup barrier.
+        if (gi == 0) {
+            const uint16_t *src = reinterpret_cast<const uint16_t *>(t.lut);
+            const uint32_t mask = (1u << max_len) - 1u;
+            if (R == 4) {
+                // 256 entries, four per lane, all loads issued before the first is used
+                const uint32_t i = 4u * lane;
+                const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
+                const uint32_t ab = a | (b << 16), cd = c | (d << 16);
+                reinterpret_cast<uint32_t *>(sym_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x06040200u);
+                reinterpret_cast<uint32_t *>(len_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x07050301u);
+            } else {
+                // 4096 entries; R = 2 implies max_len >= 9, so any 16 consecutive entries stay consecutive under the mask
+                for (uint32_t i = 16u * lane; i < Code<R>::kEntries; i += 16u * 64u) {
+                    const uint4 *v = reinterpret_cast<const uint4 *>(src + (i & mask));
+                    const uint4 x = v[0], y = v[1];
+                    uint4 sy, le;
+                    sy.x = __builtin_amdgcn_perm(x.y, x.x, 0x06040200u); le.x = __builtin_amdgcn_perm(x.y, x.x, 0x07050301u);
+                    sy.y = __builtin_amdgcn_perm(x.w, x.z, 0x06040200u); le.y = __builtin_amdgcn_perm(x.w, x.z, 0x07050301u);
+                    sy.z = __builtin_amdgcn_perm(y.y, y.x, 0x06040200u); le.z = __builtin_amdgcn_perm(y.y, y.x, 0x07050301u);
+                    sy.w = __builtin_amdgcn_perm(y.w, y.z, 0x06040200u); le.w = __builtin_amdgcn_perm(y.w, y.z, 0x07050301u);
+                    *reinterpret_cast<uint4 *>(sym_tab + i) = sy;
+                    *reinterpret_cast<uint4 *>(len_tab + i) = le;
+                }
+            }
+        }
+
+        if (n_held) {
+            uint4 *dst = reinterpret_cast<uint4 *>(words);
+            if (lane < n_held) dst[lane] = held_a;
+            if (lane + 64 < n_held) dst[lane + 64] = held_b;
+        }
+        // LDS written by some lanes of this wave is read by others: order the LDS accesses only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+        if (!active) continue;
+
+        uint16_t *out_base = t.out + v0 + lane * 8u;
+
+        Decoder<R> dec;
+        dec.words = words; dec.last_word = P.stream_cap_words - 1u;
+        if (mode == ZM_MODE_CODED) {
+            // a6: this lane's bitstream has 8 * tiles + quantum * (its length byte) bits and starts where
+            // the bitstreams of the lanes below it end
+            const uint32_t units = reinterpret_cast<const uint8_t *>(words)[lane];
+            dec.start(wave_exclusive_sum(8u * tiles + quantum * units));
+        }
+
+        if (mode == ZM_MODE_CODED && full) {
+            // Common case, straight-line: a coded stream of whole groups of kGroup tiles (one group at the
+            // default stream length).  The first group's loads were issued above; from here on the wave only
+            // computes and stores, and asks for the next group's sign-mantissa bytes when a group is done.
+            const uint32_t groups = sn / (kGroup * kTile);
+            for (uint32_t q = 0;;) {
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) {
-            const uint32_t tile = g0 + k;
-            if (tile < tiles) {
-                const int32_t left = mine - static_cast<int32_t>(tile * kTile);
-                uint2 ev = make_uint2(0u, 0u);
-                if (mode == ZM_MODE_CODED) ev = dec.tile(len_tab, sym_tab);
-                else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
-                if (left >= 8) recover_and_store<kStreaming>(out_base + tile * kTile, ev, sm[k]);
-                else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, sm[k], left);
+                for (int k = 0; k < kGroup; ++k)
+                    recover_and_store<kStreaming>(out_base + (q * kGroup + k) * kTile, dec.tile(len_tab, sym_tab), sm[k]);
+                if (++q == groups) break;
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (q * kGroup + k) * kTile);
+            }
+        } else {
+            // General case: raw chunks, short last streams, streams that are not whole groups of kGroup tiles.
+            for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
+                if (g0) {
+#pragma unroll
+                    for (int k = 0; k < kGroup; ++k) {
+                        sm[k] = make_uint2(0u, 0u);
+                        if (g0 + k < tiles && mine - static_cast<int32_t>((g0 + k) * kTile) > 0)
+                            sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (g0 + k) * kTile);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < kGroup; ++k) {
+                    const uint32_t tile = g0 + k;
+                    if (tile < tiles) {
+                        const int32_t left = mine - static_cast<int32_t>(tile * kTile);
+                        uint2 ev = make_uint2(0u, 0u);
+                        if (mode == ZM_MODE_CODED) ev = dec.tile(len_tab, sym_tab);
+                        else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
+                        if (left >= 8) recover_and_store<kStreaming>(out_base + tile * kTile, ev, sm[k]);
+                        else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, sm[k], left);
+                    }
+                }
             }
         }
+        // the next stream's bytes overwrite this one's in LDS: this wave's reads come first
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -375,15 +404,28 @@ __global__ void __launch_bounds__(256) zm_recover_kernel(const uint8_t *__restri
     }
 }
 
-inline size_t stream_cap_words(uint32_t stream_values, uint32_t max_len_bound)
+// LDS words a wave reserves for one stream of the launch's longest kind: the length bytes, the code bits
+// of a lane bounded by the longest code, the rounding of every lane to the quantum, the padding to 16 bytes,
+// and two words a lane may read past its last one.
+inline size_t stream_cap_words(uint32_t stream_values, uint32_t max_len_bound, uint32_t quantum)
 {
     const size_t syms = static_cast<size_t>(stream_values / kTile) * 8;
-    const size_t words = 64 * (2 + (syms * max_len_bound + 31) / 32) + 4;
-    return (words + 3) & ~static_cast<size_t>(3);
+    const size_t bytes = kLaneBytes + (64 * (syms * max_len_bound + quantum) + 7) / 8 + 16 + 8;
+    return ((bytes + 15) & ~static_cast<size_t>(15)) / 4;
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;
 constexpr uint64_t kLastLevelCacheBytes = 256ull << 20;   // MI355X Infinity Cache
+
+template <int R, int kWaves, bool kStreaming>
+int launch_kernel(const Launch &L, uint32_t blocks, size_t lds, hipStream_t stream)
+{
+    void *args[] = {const_cast<Launch *>(&L)};
+    const void *fn = L.streams_per_wave > 1 ? reinterpret_cast<const void *>(&zm_decode_kernel<R, kWaves, kStreaming, true>)
+                                            : reinterpret_cast<const void *>(&zm_decode_kernel<R, kWaves, kStreaming, false>);
+    // the launch's own status: an error left behind by an earlier, unrelated call is not this call's
+    return hipLaunchKernel(fn, dim3(blocks, L.n_tasks), dim3(64 * kWaves), args, lds, stream) == hipSuccess ? ZM_OK : ZM_E_HIP;
+}
 
 template <int R, int kWaves>
 int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
@@ -394,65 +436,69 @@ int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
         else return ZM_E_ARG;                   // stream too long to stage in LDS
     }
     uint32_t blocks = 0;            // of the largest tensor; workgroups past a smaller tensor's end exit at once
+    uint64_t out_bytes = 0;
     for (uint32_t k = 0; k < L.n_tasks; ++k) {
-        const uint32_t b = (L.task[k].n_streams + kWaves - 1) / kWaves;
+        const uint32_t per_block = kWaves * L.streams_per_wave;
+        const uint32_t b = (L.task[k].n_streams + per_block - 1) / per_block;
         blocks = b > blocks ? b : blocks;
+        out_bytes += 2 * L.task[k].n_values;
     }
     if (!blocks) return ZM_OK;
-    uint64_t out_bytes = 0;
-    for (uint32_t k = 0; k < L.n_tasks; ++k) out_bytes += 2 * L.task[k].n_values;
-    if (out_bytes > kLastLevelCacheBytes)
-        hipLaunchKernelGGL((zm_decode_kernel<R, kWaves, true>), dim3(blocks, L.n_tasks), dim3(64 * kWaves), lds, stream, L);
-    else
-        hipLaunchKernelGGL((zm_decode_kernel<R, kWaves, false>), dim3(blocks, L.n_tasks), dim3(64 * kWaves), lds, stream, L);
-    return hipGetLastError() == hipSuccess ? ZM_OK : ZM_E_HIP;
+    return out_bytes > kLastLevelCacheBytes ? launch_kernel<R, kWaves, true>(L, blocks, lds, stream)
+                                            : launch_kernel<R, kWaves, false>(L, blocks, lds, stream);
 }
 
+// Collects the tensors of one round length and launches them, at most kMaxTasks per launch.
 template <int R>
-int launch_group(const Task *tasks, int n, hipStream_t stream)
-{
-    constexpr uint32_t kLenBound = R == 4 ? 8 : ZM_MAX_CODE_LEN;
-    int done = 0;
-    while (done < n) {
-        Launch L{};
-        uint32_t max_stream = 0;
-        int k = 0;
-        for (; k < kMaxTasks && done + k < n; ++k) {
-            L.task[k] = tasks[done + k];
-            max_stream = max_stream > L.task[k].stream_values ? max_stream : L.task[k].stream_values;
-        }
-        L.n_tasks = static_cast<uint32_t>(k);
-        const size_t cap = stream_cap_words(max_stream, kLenBound);
+struct Group {
+    static constexpr uint32_t kLenBound = R == 4 ? 8 : ZM_MAX_CODE_LEN;
+    Launch L{};
+    uint32_t max_stream = 0, max_quantum = 1;
+    hipStream_t stream;
+
+    explicit Group(hipStream_t s) : stream(s) {}
+
+    int add(const Task &t)
+    {
+        L.task[L.n_tasks++] = t;
+        max_stream = max_stream > t.stream_values ? max_stream : t.stream_values;
+        max_quantum = max_quantum > (t.code >> 8) ? max_quantum : (t.code >> 8);
+        return L.n_tasks == kMaxTasks ? flush() : ZM_OK;
+    }
+
+    int flush()
+    {
+        if (!L.n_tasks) return ZM_OK;
+        const size_t cap = stream_cap_words(max_stream, kLenBound, max_quantum);
         L.stream_cap_words = static_cast<uint32_t>(cap);
+        L.streams_per_wave = 1;
         // two streams per workgroup: measured on one MoE layer call of 118 MB, 1 / 2 / 4 / 8 waves per
         // workgroup reach 63.1 / 63.2 / 61.9 / 58.2 % of the HBM roofline (1.2 GB calls: 72.5 / 72.9 / 73.2 / 72.0 %).
         // With long codes a workgroup stages 8 KiB of tables, so four streams share them: 2 / 4 / 8 waves reach
         // 41.9 / 45.6 / 45.6 % on a 170 MB call and 52.2 / 53.8 / 52.9 % on 1.2 GB calls.
         const int rc = launch_tasks<R, R == 4 ? 2 : 4>(L, cap, stream);
-        if (rc != ZM_OK) return rc;
-        done += k;
+        L.n_tasks = 0; max_stream = 0; max_quantum = 1;
+        return rc;
     }
-    return ZM_OK;
-}
+};
 
-
-
-// Checks one tensor's description and appends its task to the group of its round length.
-int add_task(const zm_tensor_parts &pt, const zm_tensor_info &ti, void *out, Task *t4, int &n4, Task *t2, int &n2)
+// Checks one tensor's description and fills its task.  skip: the tensor is empty.
+int make_task(const zm_tensor_parts &pt, const zm_tensor_info &ti, void *out, Task &t, bool &skip)
 {
-    if (ti.n_values == 0) return ZM_OK;
+    skip = ti.n_values == 0;
+    if (skip) return ZM_OK;
     if (!pt.table || !pt.chunk_offsets || !pt.sm || !pt.echunks || !out) return ZM_E_ARG;
     if ((reinterpret_cast<uintptr_t>(pt.table) & 15) || (reinterpret_cast<uintptr_t>(pt.chunk_offsets) & 7) ||
         (reinterpret_cast<uintptr_t>(pt.sm) & 15) || (reinterpret_cast<uintptr_t>(pt.echunks) & 15) ||
         (reinterpret_cast<uintptr_t>(out) & 15)) return ZM_E_ARG;
     if (ti.stream_values == 0 || ti.stream_values % kTile || ti.chunk_values % ti.stream_values) return ZM_E_ARG;
     if (ti.max_len < 1 || ti.max_len > ZM_MAX_CODE_LEN) return ZM_E_ARG;
-    if (ti.round_symbols != (ti.max_len <= 8 ? 4u : 2u)) return ZM_E_ARG;
+    const uint32_t span = (ti.max_len - 1) * (ti.stream_values / 64);
+    if (ti.lane_quantum != (span + 254) / 255 + (span == 0)) return ZM_E_ARG;
     if (ti.e_offset > ti.blob_size || ti.sm_offset + ((ti.n_values + 255) & ~255ull) > ti.e_offset) return ZM_E_ARG;
     if (ti.table_stride != ((8u + 4u * (ti.chunk_values / ti.stream_values + 1u) + 7u) & ~7u)) return ZM_E_ARG;
     const uint64_t n_streams = (ti.n_values + ti.stream_values - 1) / ti.stream_values;
     if (n_streams > 0x7FFFFFFFull) return ZM_E_ARG;
-    Task t;
     t.lut = static_cast<const uint8_t *>(pt.table);
     t.sm = static_cast<const uint8_t *>(pt.sm);
     t.echunks = static_cast<const uint8_t *>(pt.echunks);
@@ -464,12 +510,34 @@ int add_task(const zm_tensor_parts &pt, const zm_tensor_info &ti, void *out, Tas
     t.stream_values = ti.stream_values;
     t.streams_per_chunk = ti.chunk_values / ti.stream_values;
     t.n_streams = static_cast<uint32_t>(n_streams);
-    t.max_len = ti.max_len;
-    if (ti.round_symbols == 4) t4[n4++] = t; else t2[n2++] = t;
+    t.code = ti.max_len | ti.lane_quantum << 8;
     return ZM_OK;
 }
 
 constexpr int kMaxTensorsPerCall = 256;
+
+// Tensor i of a call, as make_task wants it; implemented by the two entry points.
+template <typename Describe>
+int decode_call(int n_tensors, Describe describe, hipStream_t stream)
+{
+    // first pass: every tensor is checked before anything is launched
+    for (int i = 0; i < n_tensors; ++i) {
+        Task t; bool skip;
+        const int rc = describe(i, t, skip);
+        if (rc != ZM_OK) return rc;
+    }
+    Group<4> short_codes(stream);
+    Group<2> long_codes(stream);
+    for (int i = 0; i < n_tensors; ++i) {
+        Task t; bool skip;
+        describe(i, t, skip);
+        if (skip) continue;
+        const int rc = (t.code & 0xffu) <= 8 ? short_codes.add(t) : long_codes.add(t);
+        if (rc != ZM_OK) return rc;
+    }
+    const int rc = short_codes.flush();
+    return rc != ZM_OK ? rc : long_codes.flush();
+}
 
 }  // namespace
 
@@ -478,16 +546,8 @@ extern "C" int zm_decode_tensors(const zm_tensor_parts *parts, const zm_tensor_i
 {
     if (n_tensors == 0) return ZM_OK;
     if (!parts || !infos || !out_bf16 || n_tensors < 0 || n_tensors > kMaxTensorsPerCall) return ZM_E_ARG;
-    Task t4[kMaxTensorsPerCall], t2[kMaxTensorsPerCall];
-    int n4 = 0, n2 = 0;
-    for (int i = 0; i < n_tensors; ++i) {
-        const int rc = add_task(parts[i], infos[i], out_bf16[i], t4, n4, t2, n2);
-        if (rc != ZM_OK) return rc;
-    }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int rc = launch_group<4>(t4, n4, s);
-    if (rc != ZM_OK) return rc;
-    return launch_group<2>(t2, n2, s);
+    return decode_call(n_tensors, [&](int i, Task &t, bool &skip) { return make_task(parts[i], infos[i], out_bf16[i], t, skip); },
+                       static_cast<hipStream_t>(stream));
 }
 
 extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_offsets,
@@ -499,27 +559,20 @@ extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const
     if (!blobs || !chunk_offsets || !infos || !expert_ids || !out_bf16) return ZM_E_ARG;
     if (n_experts <= 0 || tensors_per_expert <= 0 || n_selected < 0) return ZM_E_ARG;
     if (static_cast<long>(n_selected) * tensors_per_expert > kMaxTensorsPerCall) return ZM_E_ARG;
-    Task t4[kMaxTensorsPerCall], t2[kMaxTensorsPerCall];
-    int n4 = 0, n2 = 0;
-    for (int j = 0; j < n_selected; ++j) {
-        const int e = expert_ids[j];
-        if (e < 0 || e >= n_experts) return ZM_E_ARG;
-        for (int m = 0; m < tensors_per_expert; ++m) {
-            const size_t src = static_cast<size_t>(e) * tensors_per_expert + m;
-            const size_t dst = static_cast<size_t>(j) * tensors_per_expert + m;
-            const zm_tensor_info &ti = infos[src];
-            if (ti.n_values == 0) continue;
-            if (!blobs[src]) return ZM_E_ARG;
-            const uint8_t *blob = static_cast<const uint8_t *>(blobs[src]);
-            const zm_tensor_parts pt{blob + ti.lut_offset, chunk_offsets[src], blob + ti.sm_offset, blob + ti.e_offset};
-            const int rc = add_task(pt, ti, out_bf16[dst], t4, n4, t2, n2);
-            if (rc != ZM_OK) return rc;
-        }
-    }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int rc = launch_group<4>(t4, n4, s);
-    if (rc != ZM_OK) return rc;
-    return launch_group<2>(t2, n2, s);
+    for (int j = 0; j < n_selected; ++j)
+        if (expert_ids[j] < 0 || expert_ids[j] >= n_experts) return ZM_E_ARG;
+    auto describe = [&](int i, Task &t, bool &skip) {
+        const int j = i / tensors_per_expert, m = i % tensors_per_expert;
+        const size_t src = static_cast<size_t>(expert_ids[j]) * tensors_per_expert + m;
+        const zm_tensor_info &ti = infos[src];
+        skip = ti.n_values == 0;
+        if (skip) return ZM_OK;
+        if (!blobs[src]) return ZM_E_ARG;
+        const uint8_t *blob = static_cast<const uint8_t *>(blobs[src]);
+        const zm_tensor_parts pt{blob + ti.lut_offset, chunk_offsets[src], blob + ti.sm_offset, blob + ti.e_offset};
+        return make_task(pt, ti, out_bf16[i], t, skip);
+    };
+    return decode_call(n_selected * tensors_per_expert, describe, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int zm_recover(const void *exponents, const void *sign_mantissa, size_t n_values, void *out_bf16, void *stream)
@@ -531,8 +584,10 @@ extern "C" int zm_recover(const void *exponents, const void *sign_mantissa, size
     const uint64_t per_block = 4ull * kRecoverTilesPerWave * kTile;
     const uint64_t blocks = (n_values + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFFull) return ZM_E_ARG;
-    hipLaunchKernelGGL(zm_recover_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint8_t *>(exponents), static_cast<const uint8_t *>(sign_mantissa),
-                       static_cast<uint16_t *>(out_bf16), static_cast<uint64_t>(n_values));
-    return hipGetLastError() == hipSuccess ? ZM_OK : ZM_E_HIP;
+    const uint8_t *e = static_cast<const uint8_t *>(exponents), *sm = static_cast<const uint8_t *>(sign_mantissa);
+    uint16_t *out = static_cast<uint16_t *>(out_bf16);
+    uint64_t n = n_values;
+    void *args[] = {&e, &sm, &out, &n};
+    return hipLaunchKernel(reinterpret_cast<const void *>(&zm_recover_kernel), dim3(static_cast<uint32_t>(blocks)), dim3(256),
+                           args, 0, static_cast<hipStream_t>(stream)) == hipSuccess ? ZM_OK : ZM_E_HIP;
 }

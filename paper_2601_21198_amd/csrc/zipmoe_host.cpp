@@ -20,7 +20,7 @@
 namespace {
 
 constexpr uint32_t kMagic = 0x454F4D5Au;   // "ZMOE"
-constexpr uint32_t kVersion = 2;
+constexpr uint32_t kVersion = 3;
 constexpr uint32_t kHeaderBytes = 128;
 constexpr uint32_t kLanes = 64;
 constexpr uint32_t kRun = 8;               // consecutive values per lane per tile
@@ -29,7 +29,7 @@ constexpr uint32_t kTile = kLanes * kRun;  // 512
 // header field positions
 struct Hdr {
     static constexpr size_t magic = 0, version = 4, n_values = 8, chunk = 16, stream = 20, n_chunks = 24,
-                            max_len = 28, round_syms = 32, n_present = 36, pad_sym = 40, table_stride = 44, len_off = 48,
+                            max_len = 28, quantum = 32, n_present = 36, pad_sym = 40, table_stride = 44, len_off = 48,
                             lut_off = 56, table_off = 64, sm_off = 72, e_off = 80, blob_size = 88;
 };
 
@@ -49,7 +49,13 @@ inline uint32_t table_stride_for(uint32_t chunk_values, uint32_t stream_values)
     return static_cast<uint32_t>(align_up(8 + 4ull * (chunk_values / stream_values + 1), 8));
 }
 
-inline uint32_t round_symbols_for(uint32_t max_len) { return max_len <= 8 ? 4u : 2u; }
+// Unit of the per-lane length bytes: the smallest q >= 1 for which (L - 1) * (W / 64) <= 255 * q, so that
+// the byte of a lane whose every code has the longest length still fits.
+inline uint32_t lane_quantum_for(uint32_t max_len, uint32_t stream_values)
+{
+    const uint32_t span = (max_len - 1) * (stream_values / kLanes);
+    return std::max(1u, (span + 254) / 255);
+}
 
 // Canonical code table derived from code lengths.
 struct Book {
@@ -103,73 +109,52 @@ void fill_decode_table(const Book &b, uint8_t *lut /* 2 << max_len bytes */)
     }
 }
 
-// Scratch reused across the streams of one zm_encode call.
-struct Weaver {
-    std::vector<uint32_t> lane_words;   // [kLanes][stride]
-    std::vector<uint64_t> takers;       // per round: lanes that take a word after it
-    size_t stride = 0;
-
-    void prepare(uint32_t stream_values)
-    {
-        const size_t syms = static_cast<size_t>(stream_values / kTile) * kRun;
-        stride = 3 + (syms * ZM_MAX_CODE_LEN + 31) / 32;
-        lane_words.assign(kLanes * stride, 0);
-        takers.assign(syms + 1, 0);
-    }
-
-    // Weaves exponents e[0..n) into out; returns the number of 32-bit words (multiple of 4).
-    size_t weave(const uint8_t *e, uint32_t n, const Book &b, uint32_t *out)
-    {
-        const uint32_t R = round_symbols_for(b.max_len);
-        const uint32_t tiles = (n + kTile - 1) / kTile;
-        const uint32_t rounds = tiles * kRun / R;
-        std::fill(takers.begin(), takers.begin() + rounds, 0);
-        for (uint32_t lane = 0; lane < kLanes; ++lane) {
-            uint32_t *w = &lane_words[lane * stride];
-            uint64_t acc = 0; uint32_t fill = 0, widx = 0, used = 0, have = 2, round = 0, in_round = 0;
-            for (uint32_t t = 0; t < tiles; ++t) {
-                const uint32_t base = t * kTile + lane * kRun;
-                for (uint32_t i = 0; i < kRun; ++i) {
-                    const uint32_t idx = base + i;
-                    const uint32_t s = idx < n ? e[idx] : b.pad;
-                    const uint32_t l = b.len[s];
-                    acc |= static_cast<uint64_t>(b.wire[s]) << fill;
-                    fill += l; used += l;
-                    if (fill >= 32) { w[widx++] = static_cast<uint32_t>(acc); acc >>= 32; fill -= 32; }
-                    if (++in_round == R) {
-                        in_round = 0;
-                        if (round + 1 < rounds && (used >> 5) + 2 > have) { takers[round] |= 1ull << lane; ++have; }
-                        ++round;
-                    }
-                }
-            }
-            w[widx++] = static_cast<uint32_t>(acc);
-            while (widx < have) w[widx++] = 0;   // words a lane is handed past its last bit are zero
-        }
-        size_t o = 0;
-        uint32_t given[kLanes];
-        for (uint32_t lane = 0; lane < kLanes; ++lane) {
-            out[o++] = lane_words[lane * stride];
-            out[o++] = lane_words[lane * stride + 1];
-            given[lane] = 2;
-        }
-        for (uint32_t r = 0; r + 1 < rounds; ++r) {
-            uint64_t m = takers[r];
-            while (m) {
-                const uint32_t lane = static_cast<uint32_t>(__builtin_ctzll(m));
-                m &= m - 1;
-                out[o++] = lane_words[lane * stride + given[lane]++];
-            }
-        }
-        while (o & 3) out[o++] = 0;
-        return o;
-    }
-};
-
-size_t stream_word_bound(uint32_t stream_values)
+// Upper bound on the bytes of one coded stream: 64 length bytes, the code bits, the rounding of every lane
+// to the quantum, the padding to 16 bytes.
+size_t stream_byte_bound(uint32_t stream_values)
 {
     const size_t syms = static_cast<size_t>(stream_values / kTile) * kRun;
-    return kLanes * (2 + (syms * ZM_MAX_CODE_LEN + 31) / 32) + 4;
+    return align_up(kLanes + (kLanes * (syms * ZM_MAX_CODE_LEN + 255) + 7) / 8, 16);
+}
+
+// Packs exponents e[0..n) of one stream: 64 length bytes, then the lanes' bitstreams back to back (LSB first),
+// zero bits to a multiple of 16 bytes.  Returns the bytes written.
+size_t pack_stream(const uint8_t *e, uint32_t n, const Book &b, uint32_t quantum, uint8_t *out)
+{
+    const uint32_t tiles = (n + kTile - 1) / kTile;
+    const uint32_t syms = tiles * kRun;                 // per lane
+    uint8_t *payload = out + kLanes;
+    uint64_t acc = 0;                                    // bits not yet written, lowest first
+    uint32_t fill = 0;
+    size_t at = 0;                                       // payload bytes written
+    auto put = [&](uint32_t bits, uint32_t count) {      // count <= 32
+        acc |= static_cast<uint64_t>(bits) << fill;
+        fill += count;
+        while (fill >= 8) { payload[at++] = static_cast<uint8_t>(acc); acc >>= 8; fill -= 8; }
+    };
+    for (uint32_t lane = 0; lane < kLanes; ++lane) {
+        uint32_t used = 0;
+        for (uint32_t t = 0; t < tiles; ++t) {
+            const uint32_t base = t * kTile + lane * kRun;
+            for (uint32_t i = 0; i < kRun; ++i) {
+                const uint32_t idx = base + i;
+                const uint32_t s = idx < n ? e[idx] : b.pad;
+                put(b.wire[s], b.len[s]);
+                used += b.len[s];
+            }
+        }
+        const uint32_t units = (used - syms + quantum - 1) / quantum;
+        out[lane] = static_cast<uint8_t>(units);
+        for (uint32_t fillers = syms + quantum * units - used; fillers; ) {
+            const uint32_t k = std::min(fillers, 32u);
+            put(0, k);
+            fillers -= k;
+        }
+    }
+    if (fill) put(0, 8 - fill);
+    const size_t total = align_up(kLanes + at, 16);
+    std::memset(payload + at, 0, total - kLanes - at);
+    return total;
 }
 
 int read_info(const uint8_t *p, size_t size, zm_tensor_info *info, Book *book_out)
@@ -182,7 +167,7 @@ int read_info(const uint8_t *p, size_t size, zm_tensor_info *info, Book *book_ou
     t.stream_values = load_le<uint32_t>(p + Hdr::stream);
     t.n_chunks = load_le<uint32_t>(p + Hdr::n_chunks);
     t.max_len = load_le<uint32_t>(p + Hdr::max_len);
-    t.round_symbols = load_le<uint32_t>(p + Hdr::round_syms);
+    t.lane_quantum = load_le<uint32_t>(p + Hdr::quantum);
     t.n_present = load_le<uint32_t>(p + Hdr::n_present);
     t.lut_offset = load_le<uint64_t>(p + Hdr::lut_off);
     t.table_offset = load_le<uint64_t>(p + Hdr::table_off);
@@ -203,7 +188,7 @@ int read_info(const uint8_t *p, size_t size, zm_tensor_info *info, Book *book_ou
     Book b;
     if (!make_book(p + kHeaderBytes, b)) return ZM_E_FORMAT;
     if (b.max_len != t.max_len || b.n_present != t.n_present) return ZM_E_FORMAT;
-    if (t.round_symbols != round_symbols_for(t.max_len)) return ZM_E_FORMAT;
+    if (t.lane_quantum != lane_quantum_for(t.max_len, t.stream_values)) return ZM_E_FORMAT;
     if (load_le<uint32_t>(p + Hdr::pad_sym) != b.pad) return ZM_E_FORMAT;
     if (b.n_present >= 2 && b.kraft != (1u << ZM_MAX_CODE_LEN)) return ZM_E_FORMAT;   // decode table must be total
     if (t.n_values > 0 && b.n_present == 0) return ZM_E_FORMAT;
@@ -246,48 +231,37 @@ void package_merge(const std::vector<uint64_t> &weight, int max_len, std::vector
 }
 
 
-// Table-driven decode of one woven stream on the host: the 64 lanes are walked round by round exactly
-// as the lock-step GPU decoder does, each lane with a 64-bit window over its own two current words.
-// lut: 2^max_len entries (symbol | length << 8).  Returns false if the stream runs out of words.
-bool unweave_stream(const uint8_t *stream, size_t n_words, uint32_t n, const uint8_t *lut, uint32_t max_len,
-                    uint8_t *e)
+// Table-driven decode of one stream on the host: the prefix sum over the length bytes gives every lane's
+// first bit; each lane is then decoded on its own through a 64-bit window.
+// lut: 2^max_len entries (symbol | length << 8).  Returns false if a lane would read past the stream.
+bool unpack_stream(const uint8_t *stream, size_t n_bytes, uint32_t n, const uint8_t *lut, uint32_t max_len,
+                   uint32_t quantum, uint8_t *e)
 {
-    auto word = [stream](size_t i) { return load_le<uint32_t>(stream + 4 * i); };
-    const uint32_t R = round_symbols_for(max_len);
     const uint32_t tiles = (n + kTile - 1) / kTile;
-    const uint32_t rounds = tiles * kRun / R;
+    const uint32_t syms = tiles * kRun;
     const uint32_t mask = (1u << max_len) - 1u;
-    if (n_words < 2 * kLanes) return false;
-    uint64_t window[kLanes];      // bits of the lane's stream from its current word on
-    uint32_t pos[kLanes];         // bits of the current word already used
+    if (n_bytes < kLanes) return false;
+    const uint8_t *payload = stream + kLanes;
+    const uint64_t payload_bits = (n_bytes - kLanes) * 8ull;
+    auto window = [&](uint64_t bit) {                    // the 32 bits from `bit` on (zeros past the end)
+        uint64_t w = 0;
+        const uint64_t byte = bit >> 3;
+        for (uint32_t k = 0; k < 5 && byte + k < n_bytes - kLanes; ++k) w |= static_cast<uint64_t>(payload[byte + k]) << (8 * k);
+        return static_cast<uint32_t>(w >> (bit & 7));
+    };
+    uint64_t start = 0;
     for (uint32_t lane = 0; lane < kLanes; ++lane) {
-        window[lane] = word(2 * lane) | (static_cast<uint64_t>(word(2 * lane + 1)) << 32);
-        pos[lane] = 0;
-    }
-    size_t next = 2 * kLanes;
-    for (uint32_t r = 0; r < rounds; ++r) {
-        const uint32_t first_sym = r * R;
-        for (uint32_t lane = 0; lane < kLanes; ++lane) {
-            uint64_t w = window[lane] >> pos[lane];
-            uint32_t p = pos[lane];
-            for (uint32_t k = 0; k < R; ++k) {
-                const uint32_t x = static_cast<uint32_t>(w) & mask;
-                const uint32_t sym = lut[2 * x], len = lut[2 * x + 1];
-                const uint32_t j = first_sym + k;
-                const uint32_t idx = (j / kRun) * kTile + lane * kRun + (j % kRun);
-                if (idx < n) e[idx] = static_cast<uint8_t>(sym);
-                w >>= len; p += len;
-            }
-            pos[lane] = p;
+        const uint64_t span = syms + static_cast<uint64_t>(quantum) * stream[lane];
+        if (start + span > payload_bits) return false;
+        uint64_t bit = start;
+        for (uint32_t j = 0; j < syms; ++j) {
+            const uint32_t x = window(bit) & mask;
+            const uint32_t idx = (j / kRun) * kTile + lane * kRun + (j % kRun);
+            if (idx < n) e[idx] = lut[2 * x];
+            bit += lut[2 * x + 1];
         }
-        if (r + 1 == rounds) break;
-        for (uint32_t lane = 0; lane < kLanes; ++lane) {
-            if (pos[lane] >= 32) {
-                if (next >= n_words) return false;
-                window[lane] = (window[lane] >> 32) | (static_cast<uint64_t>(word(next++)) << 32);
-                pos[lane] -= 32;
-            }
-        }
+        if (bit > start + span) return false;
+        start += span;
     }
     return true;
 }
@@ -316,7 +290,7 @@ int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, const uint
         const uint32_t o0 = load_le<uint32_t>(entry + 8 + 4 * s), o1 = load_le<uint32_t>(entry + 8 + 4 * (s + 1));
         if ((o0 & 3) || o1 < o0 || o1 > end - at) return ZM_E_FORMAT;
         const uint32_t sn = std::min(t.stream_values, cn - s * t.stream_values);
-        if (!unweave_stream(h + o0, (o1 - o0) / 4, sn, lut, t.max_len, e + static_cast<size_t>(s) * t.stream_values))
+        if (!unpack_stream(h + o0, o1 - o0, sn, lut, t.max_len, t.lane_quantum, e + static_cast<size_t>(s) * t.stream_values))
             return ZM_E_FORMAT;
     }
     return ZM_OK;
@@ -417,10 +391,9 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
             sm[i] = static_cast<uint8_t>(((w >> 8) & 0x80) | (w & 0x7F));
         }
 
-        Weaver weaver;
-        weaver.prepare(stream_values);
+        const uint32_t quantum = lane_quantum_for(L, stream_values);
         const uint32_t max_streams = chunk_values / stream_values;
-        std::vector<uint32_t> coded(static_cast<size_t>(max_streams) * stream_word_bound(stream_values));
+        std::vector<uint8_t> coded(static_cast<size_t>(max_streams) * stream_byte_bound(stream_values));
         uint64_t pos = e_off;
         for (size_t c = 0; c < chunks; ++c) {
             const size_t first = c * static_cast<size_t>(chunk_values);
@@ -428,18 +401,18 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
             const uint32_t streams = (cn + stream_values - 1) / stream_values;
             const uint64_t raw_bytes = align_up(cn, 16);
             uint8_t *entry = blob + table_off + static_cast<uint64_t>(stride) * c;      // zero so far
-            size_t at = 0;                                                               // words
+            size_t at = 0;                                                               // bytes
             bool smaller = true;
             for (uint32_t s = 0; s < streams; ++s) {
-                store_le<uint32_t>(entry + 8 + 4 * s, static_cast<uint32_t>(4 * at));
+                store_le<uint32_t>(entry + 8 + 4 * s, static_cast<uint32_t>(at));
                 const uint32_t sn = std::min(stream_values, cn - s * stream_values);
-                at += weaver.weave(&expo[first + static_cast<size_t>(s) * stream_values], sn, book, &coded[at]);
-                if (4 * at >= raw_bytes) { smaller = false; break; }
+                at += pack_stream(&expo[first + static_cast<size_t>(s) * stream_values], sn, book, quantum, &coded[at]);
+                if (at >= raw_bytes) { smaller = false; break; }
             }
             uint64_t mode;
             if (smaller) {
-                store_le<uint32_t>(entry + 8 + 4 * streams, static_cast<uint32_t>(4 * at));
-                std::memcpy(blob + pos, coded.data(), 4 * at);
+                store_le<uint32_t>(entry + 8 + 4 * streams, static_cast<uint32_t>(at));
+                std::memcpy(blob + pos, coded.data(), at);
                 mode = ZM_MODE_CODED;
             } else {
                 std::memset(entry, 0, stride);
@@ -448,7 +421,7 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
                 mode = ZM_MODE_RAW;
             }
             store_le<uint64_t>(entry, pos | mode);
-            pos += smaller ? 4 * at : raw_bytes;
+            pos += smaller ? at : raw_bytes;
         }
         store_le<uint64_t>(blob + table_off + static_cast<uint64_t>(stride) * chunks, pos);
         const uint64_t total = align_up(pos, 256);
@@ -461,7 +434,7 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
         store_le<uint32_t>(blob + Hdr::stream, stream_values);
         store_le<uint32_t>(blob + Hdr::n_chunks, static_cast<uint32_t>(chunks));
         store_le<uint32_t>(blob + Hdr::max_len, L);
-        store_le<uint32_t>(blob + Hdr::round_syms, round_symbols_for(L));
+        store_le<uint32_t>(blob + Hdr::quantum, quantum);
         store_le<uint32_t>(blob + Hdr::n_present, book.n_present);
         store_le<uint32_t>(blob + Hdr::pad_sym, book.pad);
         store_le<uint32_t>(blob + Hdr::table_stride, stride);
@@ -499,7 +472,7 @@ int zm_validate_blob(const void *blob_host, size_t size)
     if (std::memcmp(lut.data(), p + t.lut_offset, lut.size())) return ZM_E_FORMAT;
     // chunk table and chunk structure
     uint64_t expect = t.e_offset;
-    const uint64_t word_cap = stream_word_bound(t.stream_values);
+    const uint64_t byte_cap = stream_byte_bound(t.stream_values);
     for (uint64_t c = 0; c < t.n_chunks; ++c) {
         const uint8_t *entry = p + t.table_offset + static_cast<uint64_t>(t.table_stride) * c;
         const uint64_t ent = load_le<uint64_t>(entry);
@@ -517,8 +490,14 @@ int zm_validate_blob(const void *blob_host, size_t size)
             for (uint64_t s = 0; s < streams; ++s) {
                 const uint32_t o0 = load_le<uint32_t>(entry + 8 + 4 * s), o1 = load_le<uint32_t>(entry + 8 + 4 * (s + 1));
                 if ((o0 & 15) || (o1 & 15) || o1 < o0 || o1 > end - at) return ZM_E_FORMAT;
-                const uint64_t words = (o1 - o0) / 4;
-                if (words < 2 * kLanes || words > word_cap) return ZM_E_FORMAT;
+                if (o1 - o0 < kLanes || o1 - o0 > byte_cap) return ZM_E_FORMAT;
+                // the lanes' bit counts must fit the stream: a decoder reads no lane past the stream's end
+                const uint64_t sn = std::min<uint64_t>(t.stream_values, cn - s * t.stream_values);
+                const uint64_t syms = (sn + kTile - 1) / kTile * kRun;
+                const uint8_t *lane_bytes = p + at + o0;
+                uint64_t bits = 0;
+                for (uint32_t lane = 0; lane < kLanes; ++lane) bits += syms + static_cast<uint64_t>(t.lane_quantum) * lane_bytes[lane];
+                if (align_up(kLanes + (bits + 7) / 8, 16) != o1 - o0) return ZM_E_FORMAT;
             }
         } else return ZM_E_FORMAT;
         for (uint64_t j = 8 + 4 * used_slots; j < t.table_stride; j += 4) if (load_le<uint32_t>(entry + j)) return ZM_E_FORMAT;

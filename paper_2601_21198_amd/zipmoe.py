@@ -35,7 +35,7 @@ class TensorInfo(ctypes.Structure):
     _fields_ = [("n_values", ctypes.c_uint64), ("blob_size", ctypes.c_uint64), ("lut_offset", ctypes.c_uint64),
                 ("table_offset", ctypes.c_uint64), ("sm_offset", ctypes.c_uint64), ("e_offset", ctypes.c_uint64),
                 ("chunk_values", ctypes.c_uint32), ("stream_values", ctypes.c_uint32), ("n_chunks", ctypes.c_uint32),
-                ("max_len", ctypes.c_uint32), ("round_symbols", ctypes.c_uint32), ("n_present", ctypes.c_uint32),
+                ("max_len", ctypes.c_uint32), ("lane_quantum", ctypes.c_uint32), ("n_present", ctypes.c_uint32),
                 ("table_stride", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 

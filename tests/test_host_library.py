@@ -72,7 +72,7 @@ def test_blobs_identical_to_reference_and_decodable(kind, n):
         info = zm.blob_info(blob)
         h = zo.header(blob)
         assert (info.n_values, info.chunk_values, info.stream_values, info.n_chunks, info.max_len,
-                info.round_symbols, info.n_present) == (n, C, W, h["n_chunks"], h["L"], h["R"], h["n_present"])
+                info.lane_quantum, info.n_present) == (n, C, W, h["n_chunks"], h["L"], h["quantum"], h["n_present"])
         assert (info.lut_offset, info.table_offset, info.sm_offset, info.e_offset, info.blob_size) == \
                (h["lut_offset"], h["table_offset"], h["sm_offset"], h["e_offset"], h["blob_size"])
         table = blob[h["table_offset"]: h["table_offset"] + h["table_stride"] * (h["n_chunks"] + 1)].view("<u8")
