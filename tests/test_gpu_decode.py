@@ -50,7 +50,9 @@ SIZES = [0, 1, 7, 8, 9, 511, 512, 513, 4095, 4096, 4097, 9000, 3 * 16384 + 1234]
 
 
 @pytest.mark.parametrize("C,W,max_len", [(4096, 4096, 8), (16384, 4096, 8), (4096, 1024, 12), (2048, 512, 8),
-                                         (16384, 16384, 8), (8192, 2048, 12), (32768, 8192, 12)])
+                                         (16384, 16384, 8), (8192, 2048, 12), (32768, 8192, 12),
+                                         # streams so long that fewer of them share a workgroup
+                                         (16384, 16384, 12), (32768, 32768, 12), (32768, 32768, 8)])
 def test_edge_cases_bit_exact(C, W, max_len):
     tensors, blobs = [], []
     for kind in KINDS:
@@ -99,6 +101,39 @@ def test_mixed_geometries_in_one_call():
     got = gpu_decode_tensors(blobs)
     for w, blob, g in zip(tensors, blobs, got):
         assert np.array_equal(g, w) and np.array_equal(g, zo.decode(blob))
+
+
+@pytest.mark.parametrize("kind,W,max_len", [("gauss", 4096, 8), ("wide", 4096, 12), ("wide", 16384, 12),
+                                            ("wide", 32768, 12), ("gauss", 32768, 8)])
+def test_outputs_larger_than_the_last_level_cache(kind, W, max_len):
+    """a call that writes more than 256 MB takes the launch variant with non-temporal stores; every workgroup
+    width is covered (streams of 16384 and 32768 values leave room for fewer streams per workgroup)"""
+    import torch
+    unit = synth.special_tensor(kind, (1 << 20) + 12345, seed=W + max_len)
+    tensors = [np.tile(unit, 45)[: 45 * (1 << 20) + 777 * i] for i in range(3)]          # 3 x 47 M values: 283 MB of bf16
+    say(f"{kind} W={W} L<={max_len}: compressing 3 x {tensors[0].size} values")
+    with ThreadPoolExecutor(3) as ex:
+        blobs = list(ex.map(lambda w: zm.compress(w, 32768, W, max_len)[0], tensors))
+    assert sum(2 * w.size for w in tensors) > 256 << 20
+    layer = zm.ExpertLayer([blobs], validate=False)
+    for b in blobs:
+        zm.validate_blob(b)
+        assert (zm.blob_info(b[:384]).max_len > 8) == (kind == "wide")       # "wide" takes the long-code kernels
+    bufs, starts, vals = layer.alloc_outputs(1)
+    bufs[0].fill_(0x3333)
+    layer.decode([0], bufs, starts, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = bufs[0].cpu().numpy().view(np.uint16)
+    say("decoding with the reference codec")
+    for m, (w, blob) in enumerate(zip(tensors, blobs)):
+        g = got[starts[m]: starts[m] + vals[m]]
+        assert np.array_equal(g, w)
+        h = zo.header(blob)
+        ref = np.zeros(w.size, np.uint16)
+        step = -(-h["n_chunks"] // 64)
+        with ThreadPoolExecutor(16) as ex:
+            list(ex.map(lambda c0: zo.decode_chunks(blob, c0, min(h["n_chunks"], c0 + step), ref), range(0, h["n_chunks"], step)))
+        assert np.array_equal(g, ref)
 
 
 def test_bad_arguments_are_refused_on_the_host():

@@ -1,8 +1,9 @@
 """GPU parity at the full sizes of configurations 4 and 5, in the launch shape bench.py times.
 
 Every call's output is compared on the device with the original tensors (the codec is lossless, so the
-original is the unique correct result), and sampled chunk ranges are decoded by the reference codec on
-the host and compared element by element."""
+original is the unique correct result).  One complete call of configuration 4 and one complete call on each
+sampled layer of configuration 5 are decoded by the reference codec on the host, all chunks of every tensor,
+and compared element by element; further calls are sampled by chunk ranges."""
 import sys
 from concurrent.futures import ThreadPoolExecutor
 
@@ -34,6 +35,23 @@ def build_layer(wl, layer, workers=16):
         res = list(ex.map(one, range(wl.n_experts)))
     originals = [torch.from_numpy(r[1]).cuda() for r in res]
     return [r[0] for r in res], originals
+
+
+def oracle_full_check(blobs_of_expert, got_flat, starts, workers=16):
+    """every chunk of every tensor of one expert through the reference decoder (chunk ranges spread over
+    host threads), compared element by element"""
+    jobs = []
+    for m, blob in enumerate(blobs_of_expert):
+        h = zo.header(blob)
+        ref = np.zeros(h["n_values"], np.uint16)
+        step = max(1, -(-h["n_chunks"] // (4 * workers)))
+        for c0 in range(0, h["n_chunks"], step):
+            jobs.append((blob, c0, min(h["n_chunks"], c0 + step), ref))
+        jobs.append((m, h["n_values"], ref))
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(lambda j: zo.decode_chunks(*j), [j for j in jobs if len(j) == 4]))
+    for m, n, ref in [j for j in jobs if len(j) == 3]:
+        assert np.array_equal(got_flat[starts[m]: starts[m] + n], ref), m
 
 
 def oracle_sample_check(rng, blobs_of_expert, got_flat, starts, n_ranges=6, span=4):
@@ -71,7 +89,11 @@ def test_config4_thousand_calls_top2():
         layer.decode(ids, bufs, starts, stream)
         for j, e in enumerate(ids):
             assert torch.equal(bufs[j], originals[int(e)]), (call, int(e))
-        if call in (0, 499, 999):
+        if call == 0:
+            say(f"config 4 call 0: experts {ids.tolist()} equal to the originals; the reference decoder decodes the whole call")
+            for j, e in enumerate(ids):
+                oracle_full_check(blobs[int(e)], bufs[j].cpu().numpy().view(np.uint16), starts)
+        if call in (499, 999):
             say(f"config 4 call {call}: experts {ids.tolist()} equal to the originals; sampling the reference decoder")
             for j, e in enumerate(ids):
                 oracle_sample_check(rng, blobs[int(e)], bufs[j].cpu().numpy().view(np.uint16), starts)
@@ -105,7 +127,10 @@ def test_config5_full_model_256_steps_top4():
             layers[l].decode(ids, bufs, starts, stream)
             for j, e in enumerate(ids):
                 ok &= (bufs[j] == originals[l][int(e)]).all()
-            if l in sample_layers and step in (0, 255):
+            if l in sample_layers and step == 0:             # the whole call through the reference decoder
+                for j, e in enumerate(ids):
+                    oracle_full_check(keep_blobs[l][int(e)], bufs[j].cpu().numpy().view(np.uint16), starts)
+            if l in sample_layers and step == 255:
                 for j, e in enumerate(ids[:2]):
                     oracle_sample_check(rng, keep_blobs[l][int(e)], bufs[j].cpu().numpy().view(np.uint16), starts, 3, 2)
         if step % 32 == 31:
