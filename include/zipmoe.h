@@ -214,6 +214,27 @@ typedef struct zm_tensor_parts {
 int zm_decode_tensors(const zm_tensor_parts *parts, const zm_tensor_info *infos, int n_tensors,
                       void *const *out_bf16, void *stream);
 
+/* For callers that can not allocate device memory -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc -- and have the serialised tensors in HOST memory: the same decode as
+ * zm_decode_tensors, with the compressed bytes staged in a fixed device array that belongs to the library
+ * (ZM_STAGING_BYTES bytes per device, held from the first call on that device until the process ends)
+ * instead of a caller-provided arena as in zm_cache_fetch.
+ *   host_blobs  host array [n_tensors] of HOST pointers to validated blobs (pinned memory makes the copies
+ *               asynchronous); infos[i] from zm_blob_info; out_bf16[i] a DEVICE pointer, 16-byte aligned,
+ *               that receives tensor i's n_values bf16 words.  At most 256 tensors.
+ * On `stream` it enqueues one host-to-device copy per tensor (the blob from its decode table on) and the
+ * decode launches; it calls no allocating routine.  The host blobs must stay unchanged until the stream
+ * has passed the call.  All calls on one device share that device's staging area: calls on different
+ * streams (or threads) that can overlap in time race and must be serialised by the caller; calls on one
+ * stream are ordered by the stream.  Nothing in the area needs clearing: every byte a launch reads was
+ * written by that call's copies.
+ * ZM_E_SIZE if the blobs of one call add up to more than ZM_STAGING_BYTES; ZM_E_ARG for null pointers,
+ * inconsistent infos or too many tensors; ZM_E_HIP if the runtime refuses the symbol lookup, a copy or a
+ * launch. */
+#define ZM_STAGING_BYTES (32u << 20)
+int zm_decode_host_tensors(const void *const *host_blobs, const zm_tensor_info *infos, int n_tensors,
+                           void *const *out_bf16, void *stream);
+
 /* ---- Compression-aware expert cache (Sec. 3.2, Sec. 3.4, Sec. 6) --------------
  * One cache serves one MoE layer.  HBM is partitioned into four pools, ordered
  * F < C < S < E: F keeps recovered bf16 tensors, C keeps E-chunks and SM-chunks,

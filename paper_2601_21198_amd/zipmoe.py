@@ -19,9 +19,10 @@ OK, E_ARG, E_SIZE, E_FORMAT, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5
 MAX_CODE_LEN = 12
 TILE_VALUES = 512
 MODE_CODED, MODE_RAW = 0, 1
+STAGING_BYTES = 32 << 20
 
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
-           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors",
+           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors", "zm_decode_host_tensors",
            "zm_decode_exponents_host", "zm_recover", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_image_bytes",
            "zm_cache_pack_expert", "zm_cache_create",
            "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy", "zm_plan_selection_probabilities",
@@ -117,6 +118,8 @@ def lib() -> ctypes.CDLL:
                                         c.POINTER(c.c_void_p), c.c_void_p]
         L.zm_decode_tensors.argtypes = [c.POINTER(TensorParts), c.POINTER(TensorInfo), c.c_int,
                                         c.POINTER(c.c_void_p), c.c_void_p]
+        L.zm_decode_host_tensors.argtypes = [c.POINTER(c.c_void_p), c.POINTER(TensorInfo), c.c_int,
+                                             c.POINTER(c.c_void_p), c.c_void_p]
         L.zm_decode_exponents_host.argtypes = [c.c_void_p, c.c_size_t, c.c_uint32, c.c_uint32, u8p, c.c_int]
         L.zm_recover.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
         L.zm_cache_dispatch.argtypes = [u64p, c.c_int, c.POINTER(c.c_int32), c.c_int, c.c_int]
@@ -260,6 +263,12 @@ def recover(exponents_ptr: int, sign_mantissa_ptr: int, n_values: int, out_ptr: 
 def decode_tensors(parts, infos, n_tensors: int, out_bf16, stream: int = 0) -> None:
     """zm_decode_tensors with ready-made ctypes arrays."""
     _check(lib().zm_decode_tensors(parts, infos, n_tensors, out_bf16, ctypes.c_void_p(stream)), "zm_decode_tensors")
+
+
+def decode_host_tensors(host_blobs, infos, n_tensors: int, out_bf16, stream: int = 0) -> None:
+    """zm_decode_host_tensors with ready-made ctypes arrays."""
+    _check(lib().zm_decode_host_tensors(host_blobs, infos, n_tensors, out_bf16, ctypes.c_void_p(stream)),
+           "zm_decode_host_tensors")
 
 
 class ExpertLayer:
