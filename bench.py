@@ -162,7 +162,7 @@ def bench_split(args, wl, workers: int, steps: int, warmup: int) -> int:
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic("split-" + args.workload),
                      "kernel": "zm_recover_kernel",
-                     "kernel_us": round(kernel_s * 1e6, 2), "algorithmic_bytes_per_launch": alg},
+                     "us_per_launch": round(kernel_s * 1e6, 2), "algorithmic_bytes_per_launch": alg},
         "host_decode": {"value": round(2.0 * n_total / host_dt / 1e9, 3), "unit": "GB/s of bf16", "threads": workers,
                         "note": "zm_decode_exponents_host over the same tensors, one after the other"},
     }), flush=True)
@@ -303,7 +303,9 @@ def main() -> int:
     ap.add_argument("--stream-values", type=int, default=4096)
     ap.add_argument("--max-len", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--verify", action="store_true", help="compare the last step's output with the originals")
+    ap.add_argument("--no-verify", action="store_true", help="skip the comparison of the last calls' outputs with the originals")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the runs beside the reported one: default store policy, cache-warm outputs, mover ceiling")
     ap.add_argument("--path", default="fused", choices=["fused", "split", "cache"],
                     help="fused: zm_decode_experts (default, the line the driver reads); split: the paper's own "
                          "division of work -- zm_decode_exponents_host on host threads, zm_recover on the GPU; "
@@ -366,55 +368,132 @@ def main() -> int:
 
     # ---- pre-marshalled calls: one per (step, layer); routing differs from call to call
     stream = torch.cuda.current_stream().cuda_stream
-    out_sets = [layers[0].alloc_outputs(wl.top_k) for _ in range(2)]        # two output sets, alternated
+    out_bytes_per_call = 2 * wl.top_k * wl.values_per_expert()
+    # cold outputs: enough output sets that a buffer has left the 256 MB last-level cache before it is written again
+    n_cold_sets = max(2, -(-(512 << 20) // out_bytes_per_call) + 1)
+    cold_sets = [layers[0].alloc_outputs(wl.top_k) for _ in range(n_cold_sets)]
     n_distinct = min(steps + warmup, 64)
-    calls, call_bytes, call_out_bytes = [], [], []
+    routes = [[synth.route(wl, layer, s) for layer in range(wl.n_layers)] for s in range(n_distinct)]
+    call_bytes, call_out_bytes, call_read_bytes = [], [], []
     for s in range(n_distinct):
-        per_step = []
         for layer in range(wl.n_layers):
-            ids = synth.route(wl, layer, s)
-            bufs, starts, _ = out_sets[(s * wl.n_layers + layer) % 2]
-            per_step.append(layers[layer].make_call(ids, bufs, starts))
-            ob = sum(2 * n_values[layer][int(e)] for e in ids)
+            ob = sum(2 * n_values[layer][int(e)] for e in routes[s][layer])
+            rb = sum(read_bytes[layer][int(e)] for e in routes[s][layer])
             call_out_bytes.append(ob)
-            call_bytes.append(ob + sum(read_bytes[layer][int(e)] for e in ids))
-        calls.append(per_step)
+            call_read_bytes.append(rb)
+            call_bytes.append(ob + rb)
 
-    def run(k0: int, k: int) -> None:
-        for s in range(k0, k0 + k):
+    def make_calls(sets, stores):
+        return [[layers[layer].make_call(routes[s][layer], *sets[(s * wl.n_layers + layer) % len(sets)][:2], stores)
+                 for layer in range(wl.n_layers)] for s in range(n_distinct)]
+
+    def timed(calls, k_warm, k_steps):
+        """k_warm untimed steps, then exactly k_steps steps between two events on the launch stream"""
+        for s in range(k_warm):
             for c in calls[s % n_distinct]:
                 c(stream)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_start = time.perf_counter()
+        ev0.record(torch.cuda.current_stream())
+        for s in range(k_warm, k_warm + k_steps):
+            for c in calls[s % n_distinct]:
+                c(stream)
+        ev1.record(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_start, ev0.elapsed_time(ev1)
 
     reference_copy(args.copy_mib)
-    run(0, warmup)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_start = time.perf_counter()
-    ev0.record()
-    run(warmup, steps)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t_start
-    gpu_ms = ev0.elapsed_time(ev1)
-
     launches = steps * wl.n_layers
     idx = [((warmup + s) % n_distinct) * wl.n_layers + l for s in range(steps) for l in range(wl.n_layers)]
     out_bytes = float(sum(call_out_bytes[i] for i in idx))
     alg_bytes = float(sum(call_bytes[i] for i in idx))
+    frac_of = lambda gpu_ms: alg_bytes / (gpu_ms / 1e3) / 1e9 / HBM_PEAK_GBPS
+
+    # the timed region the line reports: outputs rotate (nothing the kernel writes is cache-resident), and the
+    # caller says so by asking for streaming stores
+    cold_calls = make_calls(cold_sets, zm.STORES_STREAMING)
+    wall, gpu_ms = timed(cold_calls, warmup, steps)
     value = out_bytes / wall / 1e9
     kernel_s = gpu_ms / 1e3 / launches
     achieved = alg_bytes / launches / kernel_s / 1e9
 
-    if args.verify:
+    verified = None
+    if not args.no_verify:
+        # the outputs of the last calls are still in their buffers: compare them with the original tensors, and
+        # one tensor with the reference decoder's output
+        from oracle import oracle as zo
         s_last = (warmup + steps - 1) % n_distinct
-        for layer in range(wl.n_layers - 1, max(-1, wl.n_layers - 3), -1):
-            ids = synth.route(wl, layer, s_last)
-            bufs, starts, vals = out_sets[(s_last * wl.n_layers + layer) % 2]
+        checked = 0
+        for layer in range(wl.n_layers - 1, max(-1, wl.n_layers - 1 - min(3, n_cold_sets)), -1):
+            ids = routes[s_last][layer]
+            bufs, starts, vals = cold_sets[(s_last * wl.n_layers + layer) % n_cold_sets]
             for j, e in enumerate(ids):
                 got = bufs[j].cpu().numpy().view(np.uint16)
                 for m, t in enumerate(synth.expert_tensors(wl, layer, int(e))):
-                    assert np.array_equal(got[starts[m]: starts[m] + vals[m]], t.reshape(-1)), (layer, e, m)
-        log("verify: outputs of the last step equal the original tensors")
+                    if not np.array_equal(got[starts[m]: starts[m] + vals[m]], t.reshape(-1)):
+                        raise SystemExit(f"bench.py: decoded output differs from the original (layer {layer}, expert {int(e)}, tensor {m})")
+                    checked += 1
+        # and one more call, untimed, against the reference decoder: the first call's first expert on layer 0
+        bufs, starts, vals = cold_sets[0]
+        layers[0].decode(first_ids, bufs, starts, stream, zm.STORES_STREAMING)
+        torch.cuda.synchronize()
+        got = bufs[0].cpu().numpy().view(np.uint16)
+        for m in range(layers[0].tensors_per_expert):
+            if not np.array_equal(got[starts[m]: starts[m] + vals[m]], zo.decode(sample_blobs[m])):
+                raise SystemExit(f"bench.py: decoded output differs from the reference decoder's (tensor {m})")
+        verified = (f"{checked} tensors of the last step's calls equal to the originals, "
+                    f"{layers[0].tensors_per_expert} tensors equal to the reference decoder's output")
+        log("verify: " + verified)
+
+    # the same calls with (a) the default store policy on the same rotating outputs, (b) two alternating output
+    # sets that stay in the last-level cache, default policy (what the previous figures of this benchmark were)
+    extra = {}
+    if not args.no_extra:
+        _, ms_auto = timed(make_calls(cold_sets, zm.STORES_AUTO), warmup, steps)
+        warm_sets = cold_sets[:2]
+        _, ms_warm = timed(make_calls(warm_sets, zm.STORES_AUTO), warmup, steps)
+        extra = {"frac_cold_default_stores": round(frac_of(ms_auto), 4), "frac_cache_warm": round(frac_of(ms_warm), 4),
+                 "us_per_launch_cache_warm": round(ms_warm * 1e3 / launches, 2)}
+        # practical ceiling: a plain mover of the mean call's bytes and mix, buffers rotating like the outputs
+        mean_read = int(sum(call_read_bytes[i] for i in idx) / launches) // 16 * 16
+        mean_write = int(out_bytes / launches) // 16 * 16
+        region = 768 << 20
+        src = torch.full((region,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(region, dtype=torch.uint8, device="cuda")
+        slots_r, slots_w = region // (-(-mean_read // 4096) * 4096), region // (-(-mean_write // 4096) * 4096)
+        ceiling = {}
+        for pieces in (1, 8):
+            for streaming in (False, True):
+                def mover(i):
+                    zm.mover_probe(src.data_ptr() + (i % slots_r) * (-(-mean_read // 4096) * 4096),
+                                   dst.data_ptr() + (i % slots_w) * (-(-mean_write // 4096) * 4096),
+                                   mean_read, mean_write, pieces, streaming, stream)
+                for i in range(max(20, warmup * wl.n_layers)):
+                    mover(i)
+                torch.cuda.synchronize()
+                ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                ev0.record(torch.cuda.current_stream())
+                for i in range(launches):
+                    mover(i)
+                ev1.record(torch.cuda.current_stream())
+                torch.cuda.synchronize()
+                us = ev0.elapsed_time(ev1) * 1e3 / launches
+                ceiling[f"pieces{pieces}_{'streaming' if streaming else 'ordinary'}"] = {
+                    "us_per_launch": round(us, 2), "GBps": round((mean_read + mean_write) / us / 1e3, 1)}
+        best = max(ceiling.values(), key=lambda c: c["GBps"])
+        extra["copy_ceiling"] = {"GBps": best["GBps"], "frac_of_peak": round(best["GBps"] / HBM_PEAK_GBPS, 4),
+                                 "what": "zm_mover_probe: a plain kernel reading and writing the mean call's bytes, buffers rotating "
+                                         "over 768 MB; best of the variants below", "variants": ceiling,
+                                 "read_bytes": mean_read, "write_bytes": mean_write}
+        del src, dst
+
+    # the kernel(s) one call launches, from the library's own rule
+    t_per = layers[0].tensors_per_expert
+    sel = [layers[0].infos[int(e) * t_per + m] for e in routes[0][0] for m in range(t_per)]
+    shapes = zm.decode_launch_shapes(sel, zm.STORES_STREAMING)
+    kernel_names = ["zm_decode_kernel<%d,%d,%s>" % (sh.round_symbols, sh.waves_per_workgroup, "true" if sh.streaming_stores else "false")
+                    for sh in shapes]
 
     result = {
         "metric": "decompressed bf16 GB/s per GPU; % of HBM roofline (bytes read+written)",
@@ -439,6 +518,9 @@ def main() -> int:
             "bf16_bytes_per_step": out_bytes / steps,
             "compressed_resident_bytes": compressed_total,
             "compression_ratio": round(compressed_total / raw_total, 4),
+            "outputs": f"rotate over {n_cold_sets} buffer sets ({n_cold_sets * out_bytes_per_call / 2**20:.0f} MiB): not cache-resident",
+            "stores": "streaming (zm_decode_experts_stores)",
+            "verified": verified,
         },
         "roofline": {
             "bound": "hbm",
@@ -447,10 +529,12 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": measured_traffic(args.workload),
-            "kernel": "zm_decode_kernel<4,2,%s>" % ("true" if out_bytes / launches > 256 * 2 ** 20 else "false"),
-            "kernel_us": round(kernel_s * 1e6, 2),
+            "kernel": ", ".join(kernel_names),
+            "us_per_launch": round(kernel_s * 1e6, 2),
+            "us_per_launch_is": "HIP-event time of the timed region / launches (launch gaps included)",
             "algorithmic_bytes_per_launch": alg_bytes / launches,
             "algorithmic_bytes_per_value": round(alg_bytes / (out_bytes / 2), 4),
+            **extra,
         },
     }
     if not args.no_cpu_baseline:

@@ -160,7 +160,8 @@ int zm_validate_blob(const void *blob_host, size_t size);
 
 /* The hot call (Sec. 3.1 "Real-time Inference", steps 5-8, for experts whose
  * compressed form is resident; Sec. 3.3 recovery): decode the experts a MoE
- * layer's gate selected, all in one kernel launch per code-table width class.
+ * layer's gate selected, in one kernel launch per 48 tensors of a code-table width class (codes of at most 8
+ * bits, longer codes).
  *
  *   blobs             host array [n_experts * tensors_per_expert] of DEVICE
  *                     pointers; entry e*tensors_per_expert + m is tensor m of
@@ -195,6 +196,40 @@ int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_off
                       void *const *out_bf16, void *stream);
 
 
+/* The same call with the store policy chosen by the caller, who knows what becomes of the output buffers:
+ *   ZM_STORES_AUTO       what zm_decode_experts does: non-temporal stores iff one launch writes more than the
+ *                        256 MB last-level cache holds
+ *   ZM_STORES_CACHED     ordinary stores: right when the same buffers are rewritten call after call (the lines
+ *                        are still in the last-level cache and never travel to HBM) or are read at once
+ *   ZM_STORES_STREAMING  non-temporal stores: right when the buffers are not cache-resident (fresh or rotating
+ *                        buffers): nothing is left in the L2 caches to be written back when the kernel ends
+ * ZM_E_ARG for any other value. */
+#define ZM_STORES_AUTO      0
+#define ZM_STORES_CACHED    1
+#define ZM_STORES_STREAMING 2
+int zm_decode_experts_stores(const void *const *blobs, const uint64_t *const *chunk_offsets,
+                             const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
+                             const int32_t *expert_ids, int n_selected,
+                             void *const *out_bf16, int stores, void *stream);
+
+
+/* What a decode call for the tensors infos[0..n_tensors) would launch, by the rule the decode calls use
+ * themselves and without launching anything (for benchmarks and profiles that have to name the kernel):
+ * one entry per kernel launch, in launch order.  Host only. */
+typedef struct zm_launch_shape {
+    uint32_t round_symbols;        /* symbols a lane decodes per 32-bit window: 4 (codes <= 8 bits) or 2   */
+    uint32_t waves_per_workgroup;  /* streams that share a workgroup                                       */
+    uint32_t streaming_stores;     /* 1: non-temporal stores                                               */
+    uint32_t workgroups;           /* grid x: workgroups of the largest tensor of the launch               */
+    uint32_t tensors;              /* grid y                                                               */
+    uint32_t lds_bytes;            /* LDS of one workgroup                                                 */
+} zm_launch_shape;
+/* shapes_out holds shapes_cap entries (may be NULL with 0); *n_shapes receives the number of launches, which
+ * may exceed shapes_cap.  ZM_E_ARG as for the decode calls. */
+int zm_decode_launch_shapes(const zm_tensor_info *infos, int n_tensors, int stores,
+                            zm_launch_shape *shapes_out, int shapes_cap, int *n_shapes);
+
+
 /* One tensor given by its parts instead of by one blob, for callers that keep
  * only some parts of a tensor resident (Sec. 3.2 "Compression States": the
  * E-chunks and the SM-chunks of an expert may be cached separately).  All four
@@ -213,6 +248,18 @@ typedef struct zm_tensor_parts {
  * ZM_E_ARG for null or misaligned pointers or inconsistent infos; ZM_E_HIP. */
 int zm_decode_tensors(const zm_tensor_parts *parts, const zm_tensor_info *infos, int n_tensors,
                       void *const *out_bf16, void *stream);
+
+/* Measurement aid (no part of the decode path): a plain streaming kernel that reads read_bytes from src
+ * and writes write_bytes to dst (both DEVICE, 16-byte aligned, sizes multiples of 16, write_bytes >= 16)
+ * with 128-bit vectors, ordinary or non-temporal stores.  pieces_per_lane = 1: one vector per lane and
+ * direction, the finest grain; 8: eight per lane, all loads before the first store, which is what one
+ * wavefront of the decode kernel moves for a stream of 4096 values.  Timed on a launch of the decode call's
+ * size and read/write mix it gives the practical ceiling of this machine's memory system that the decode
+ * kernel's fraction of the HBM roofline is set against.  Asynchronous on `stream`.
+ * ZM_E_ARG for null or misaligned pointers, bad sizes or another pieces_per_lane; ZM_E_HIP if the launch
+ * fails. */
+int zm_mover_probe(const void *src, void *dst, size_t read_bytes, size_t write_bytes, int pieces_per_lane,
+                   int streaming_stores, void *stream);
 
 /* For callers that can not allocate device memory -- code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc -- and have the serialised tensors in HOST memory: the same decode as

@@ -60,8 +60,7 @@ struct Task {
 struct Launch {
     uint32_t n_tasks;
     uint32_t stream_cap_words;   // LDS words reserved per wave for its stream
-    uint32_t streams_per_wave;   // consecutive streams of a tensor that one wave decodes
-    uint32_t pad;
+    uint32_t pad[2];
     Task task[kMaxTasks];        // blockIdx.y selects the task
 };
 static_assert(sizeof(Launch) <= 4096, "kernel arguments must stay under 4 KiB");
@@ -93,18 +92,24 @@ __device__ __forceinline__ void recover4(uint32_t e4, uint32_t sm4, uint32_t &w0
     w23 = __builtin_amdgcn_perm(hi4, lo4, 0x07030602u);
 }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// kStreaming: the output of the launch is larger than the last-level cache, so the stores are marked
-// non-temporal; smaller outputs are written normally and tend to stay cached for their consumer.
+// kStreaming: the stores are marked non-temporal (the output is larger than the last-level cache, or the
+// caller said that its buffers are not cache-resident); else they are ordinary stores, whose lines tend to
+// stay cached for a consumer or for the next call that rewrites the same buffers.
 template <bool kStreaming = false>
 __device__ __forceinline__ void recover_and_store(uint16_t *dst, uint2 e, uint2 sm)
 {
     uint4 w;
     recover4(e.x, sm.x, w.x, w.y);
     recover4(e.y, sm.y, w.z, w.w);
-    if constexpr (kStreaming) __builtin_nontemporal_store((u32x4){w.x, w.y, w.z, w.w}, reinterpret_cast<u32x4 *>(dst));
-    else *reinterpret_cast<uint4 *>(dst) = w;
+    if constexpr (kStreaming) {
+        // four adjacent word stores that the compiler merges into one 128-bit non-temporal store; written as a
+        // vector store the same code needs 11 more registers and loses two waves per SIMD
+        uint32_t *p = reinterpret_cast<uint32_t *>(__builtin_assume_aligned(dst, 16));
+        __builtin_nontemporal_store(w.x, p); __builtin_nontemporal_store(w.y, p + 1);
+        __builtin_nontemporal_store(w.z, p + 2); __builtin_nontemporal_store(w.w, p + 3);
+    } else {
+        *reinterpret_cast<uint4 *>(dst) = w;
+    }
 }
 
 // Same for a lane that owns fewer than eight values of the tile.
@@ -118,13 +123,13 @@ __device__ __forceinline__ void recover_and_store_partial(uint16_t *dst, uint2 e
         if (q < left) dst[q] = static_cast<uint16_t>(ws[q >> 1] >> (16 * (q & 1)));
 }
 
-template <int R>
-struct Code {
-    static constexpr int kIndexBits = R == 4 ? 8 : 12;     // R = 4 iff the longest code has at most 8 bits
-    static constexpr uint32_t kEntries = 1u << kIndexBits;
-};
+constexpr uint32_t kTableEntries = 256;   // the LDS table resolves the first eight bits of a code
 
-// Lock-step decoder state of one lane (a5).  len_tab / sym_tab are the workgroup's byte tables.
+// Lock-step decoder state of one lane (a5).
+// R = 4: every code has at most 8 bits, four symbols per 32-bit window.  R = 2: codes of up to ZM_MAX_CODE_LEN
+// bits, two symbols per window; the LDS table still resolves eight bits, and a lane that meets a longer code
+// (its table entry carries a length above 8: no code of at most 8 bits begins with these bits) takes its entry
+// from the tensor's full decode table in device memory instead.  Long codes are the rare ones by construction.
 template <int R>
 struct Decoder {
     const uint32_t *words;        // the stream as staged in LDS (length bytes included)
@@ -143,35 +148,43 @@ struct Decoder {
         next = q + 2u;
     }
 
-    // Decodes this lane's eight exponent bytes of one tile.
-    __device__ __forceinline__ uint2 tile(const uint8_t *len_tab, const uint8_t *sym_tab)
+    // Decodes this lane's eight exponent bytes of one tile.  tab: the workgroup's table, 256 entries of
+    // length | symbol << 8; full_table / max_len: the tensor's decode table (symbol | length << 8) and its
+    // index width, read only for codes longer than 8 bits.
+    __device__ __forceinline__ uint2 tile(const uint16_t *tab, const uint16_t *full_table, uint32_t max_len)
     {
-        constexpr uint32_t kMask = Code<R>::kEntries - 1u;
         uint32_t e[2] = {0u, 0u};
 #pragma unroll
         for (int r = 0; r < 8 / R; ++r) {
             // the word this lane takes if the round crosses a word boundary: asked for now, used after the round
             const uint32_t fresh = words[min(next, last_word)];
-            // R symbols out of one 32-bit window; `used` is the bit offset of the next code in it
+            // R symbols out of one 32-bit window.  acc sums the entries: its low byte is the bit offset of the
+            // next code in the window (at most 32), the bytes above hold a sum of symbols that nothing reads.
+            // The field extract takes the low five bits of acc as its offset; when they wrap (32 bits used) no
+            // further code is extracted.
             const uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
-            uint32_t used = 0;
+            uint32_t acc = 0;
             uint32_t s[R];
 #pragma unroll
             for (int k = 0; k < R; ++k) {
-                const uint32_t idx = (win >> used) & kMask;
-                s[k] = sym_tab[idx];
-                used += len_tab[idx];
+                uint32_t v = tab[__builtin_amdgcn_ubfe(win, acc, 8)];
+                if constexpr (R == 2) {
+                    if (__builtin_amdgcn_ballot_w64((v & 0xffu) > 8u)) {          // some lane of the wave has a long code
+                        if ((v & 0xffu) > 8u) {
+                            const uint32_t full = full_table[(win >> (acc & 31u)) & ((1u << max_len) - 1u)];
+                            v = __builtin_amdgcn_perm(0u, full, 0x0c0c0001u);      // symbol | length << 8  ->  length | symbol << 8
+                        }
+                    }
+                }
+                s[k] = v;
+                acc += v;
             }
-            pos += used;
-            // byte 0 of each symbol register, packed with byte permutes (0x0c selects a zero byte)
-            if constexpr (R == 4) {
-                const uint32_t s01 = __builtin_amdgcn_perm(s[1], s[0], 0x0c0c0400u);
-                e[r] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(s[3], s[2], 0x0c0c0400u), s01, 0x05040100u);
-            } else {
-                const uint32_t s01 = __builtin_amdgcn_perm(s[1], s[0], 0x0c0c0400u);
-                e[r >> 1] = (r & 1) ? __builtin_amdgcn_perm(s01, e[r >> 1], 0x05040100u) : s01;
-            }
-            // written without branches so that the whole tile is one basic block
+            pos += acc & 0xffu;
+            // byte 1 (the symbol) of each entry, packed with byte permutes (0x0c selects a zero byte)
+            const uint32_t s01 = __builtin_amdgcn_perm(s[1], s[0], 0x0c0c0501u);
+            if constexpr (R == 4) e[r] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(s[3], s[2], 0x0c0c0501u), s01, 0x05040100u);
+            else e[r >> 1] = (r & 1) ? __builtin_amdgcn_perm(s01, e[r >> 1], 0x05040100u) : s01;
+            // written without branches so that (with short codes) the whole tile is one basic block
             const bool take = pos >= 32u;
             lo = take ? hi : lo;
             hi = take ? fresh : hi;
@@ -182,17 +195,14 @@ struct Decoder {
     }
 };
 
-// R: symbols per round; kWaves: waves per workgroup; kStreaming: non-temporal stores; kLoop: a wave decodes
-// P.streams_per_wave streams, else one
-template <int R, int kWaves, bool kStreaming, bool kLoop>
+// R: symbols per round; kWaves: waves (streams) per workgroup; kStreaming: non-temporal stores
+template <int R, int kWaves, bool kStreaming>
 __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
 {
-    // Byte tables of the workgroup's tensor, at fixed LDS addresses so that a lookup is one LDS read with
-    // an immediate offset.  The lookups of a wave hit random words of a 64-word table and do collide on
-    // banks, but waves spend about 1 % of their cycles waiting for LDS: confining the lookups to 32- or
-    // 16-word tables changed nothing.
-    __shared__ __align__(16) uint8_t len_tab[Code<R>::kEntries];
-    __shared__ __align__(16) uint8_t sym_tab[Code<R>::kEntries];
+    // The decode table of the workgroup's tensor for the first eight bits of a code, at a fixed LDS address:
+    // one 16-bit read gives a code's length and its symbol.  (Two byte tables, one read each, were 2-4 % slower:
+    // twice the LDS instructions, whose random accesses collide on banks.)
+    __shared__ __align__(16) uint16_t tab[kTableEntries];
     extern __shared__ __align__(16) uint32_t stream_lds[];
 
     const uint32_t lane = threadIdx.x & 63u;
@@ -205,166 +215,142 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     const uint32_t max_len = t.code & 0xffu, quantum = t.code >> 8;
     const uint32_t stride = (8u + 4u * (t.streams_per_chunk + 1u) + 7u) & ~7u;     // bytes of a chunk-table entry
 
-    // every wave decodes streams_per_wave consecutive streams of its tensor, one after the other
-    const uint32_t per_wave = kLoop ? P.streams_per_wave : 1u;
-    const uint32_t g_first = (blockIdx.x * kWaves + wave) * per_wave;
-    for (uint32_t gi = 0; gi < per_wave; ++gi) {
-        const uint32_t g = g_first + gi;
-        bool active = g < t.n_streams;
-        const uint64_t v0 = static_cast<uint64_t>(g) * W;              // first value of the stream in the tensor
-        uint32_t sn = 0, mode = ZM_MODE_RAW, tiles = 0;
-        const uint8_t *raw = nullptr;
-        if (active) {
-            const uint64_t rest = t.n_values - v0;
-            sn = rest < W ? static_cast<uint32_t>(rest) : W;
-            tiles = (sn + kTile - 1) / kTile;
-        }
-        const bool full = sn != 0 && sn % (kGroup * kTile) == 0;       // the common shape: whole groups of eight tiles
-        const uint8_t *sm_base = t.sm + v0 + lane * 8u;
-        const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
+    const uint32_t g = blockIdx.x * kWaves + wave;
+    bool active = g < t.n_streams;
+    const uint64_t v0 = static_cast<uint64_t>(g) * W;              // first value of the stream in the tensor
+    uint32_t sn = 0, mode = ZM_MODE_RAW, tiles = 0;
+    const uint8_t *raw = nullptr;
+    if (active) {
+        const uint64_t rest = t.n_values - v0;
+        sn = rest < W ? static_cast<uint32_t>(rest) : W;
+        tiles = (sn + kTile - 1) / kTile;
+    }
+    const bool full = sn != 0 && sn % (kGroup * kTile) == 0;       // the common shape: whole groups of eight tiles
+    const uint8_t *sm_base = t.sm + v0 + lane * 8u;
+    const int32_t mine = static_cast<int32_t>(sn) - static_cast<int32_t>(lane * 8u);   // values left from this lane's first one
 
-        uint4 held_a = make_uint4(0u, 0u, 0u, 0u), held_b = held_a;   // first 2 KiB of the stream
-        uint32_t n_held = 0;
-        if (active) {
-            const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
-            // one read of the chunk's table entry gives the chunk's place and mode and this stream's extent
-            const uint8_t *entry = reinterpret_cast<const uint8_t *>(t.table) + static_cast<uint64_t>(c) * stride;
-            const uint64_t ent = *reinterpret_cast<const uint64_t *>(entry);
-            const uint32_t o0 = reinterpret_cast<const uint32_t *>(entry + 8)[s];
-            const uint32_t o1 = reinterpret_cast<const uint32_t *>(entry + 8)[s + 1];
-            const uint64_t at = (ent & ~15ull) - t.e_offset;            // offset inside the E-chunk region
-            mode = static_cast<uint32_t>(ent & 15ull);
-            if ((ent & ~15ull) < t.e_offset) {
+    uint4 held_a = make_uint4(0u, 0u, 0u, 0u), held_b = held_a;   // first 2 KiB of the stream
+    uint32_t n_held = 0;
+    if (active) {
+        const uint32_t c = g / t.streams_per_chunk, s = g % t.streams_per_chunk;
+        // one read of the chunk's table entry gives the chunk's place and mode and this stream's extent
+        const uint8_t *entry = reinterpret_cast<const uint8_t *>(t.table) + static_cast<uint64_t>(c) * stride;
+        const uint64_t ent = *reinterpret_cast<const uint64_t *>(entry);
+        const uint32_t o0 = reinterpret_cast<const uint32_t *>(entry + 8)[s];
+        const uint32_t o1 = reinterpret_cast<const uint32_t *>(entry + 8)[s + 1];
+        const uint64_t at = (ent & ~15ull) - t.e_offset;            // offset inside the E-chunk region
+        mode = static_cast<uint32_t>(ent & 15ull);
+        if ((ent & ~15ull) < t.e_offset) {
+            active = false;
+        } else if (mode == ZM_MODE_CODED) {
+            // a4: the stream's bytes, 128 bits per lane per load.  They are requested before the (larger)
+            // sign-mantissa bytes because decoding can not start without them; the first 2 KiB (two
+            // vectors per lane, more than a typical stream) wait in registers until the other requests
+            // are out, longer streams are copied here.
+            if (o1 < o0 + kLaneBytes || at + o1 > t.e_size) {
                 active = false;
-            } else if (mode == ZM_MODE_CODED) {
-                // a4: the stream's bytes, 128 bits per lane per load.  They are requested before the (larger)
-                // sign-mantissa bytes because decoding can not start without them; the first 2 KiB (two
-                // vectors per lane, more than a typical stream) wait in registers until the other requests
-                // are out, longer streams are copied here.
-                if (o1 < o0 + kLaneBytes || at + o1 > t.e_size) {
-                    active = false;
-                } else {
-                    const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
-                    const uint4 *src = reinterpret_cast<const uint4 *>(t.echunks + at + o0);
-                    uint4 *dst = reinterpret_cast<uint4 *>(words);
-                    n_held = min(nvec, 128u);
-                    if (lane < n_held) held_a = src[lane];
-                    if (lane + 64 < n_held) held_b = src[lane + 64];
-                    for (uint32_t i = 128 + lane; i < nvec; i += 64) dst[i] = src[i];
-                }
             } else {
-                raw = t.echunks + at + static_cast<uint64_t>(s) * W;
-                if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.e_size) active = false;
-            }
-        }
-        // Next in the request order: the sign-mantissa bytes of the first kGroup tiles.  They stay in flight
-        // while the stream is staged and decoding starts.
-        uint2 sm[kGroup];
-        if (full) {
-#pragma unroll
-            for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
-        } else {
-#pragma unroll
-            for (int k = 0; k < kGroup; ++k) {
-                sm[k] = make_uint2(0u, 0u);
-                if (static_cast<uint32_t>(k) < tiles && mine - static_cast<int32_t>(k * kTile) > 0)
-                    sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
-            }
-        }
-
-        // a3 (first stream only): decode table -> LDS, split into a length table and a symbol table and
-        // replicated over the index bits above the longest code.  Every wave of the workgroup writes the same
-        // bytes (LDS word writes are atomic), so a wave may read as soon as its own writes are done: no
-        // workgroup barrier.
-        if (gi == 0) {
-            const uint16_t *src = reinterpret_cast<const uint16_t *>(t.lut);
-            const uint32_t mask = (1u << max_len) - 1u;
-            if (R == 4) {
-                // 256 entries, four per lane, all loads issued before the first is used
-                const uint32_t i = 4u * lane;
-                const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
-                const uint32_t ab = a | (b << 16), cd = c | (d << 16);
-                reinterpret_cast<uint32_t *>(sym_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x06040200u);
-                reinterpret_cast<uint32_t *>(len_tab)[lane] = __builtin_amdgcn_perm(cd, ab, 0x07050301u);
-            } else {
-                // 4096 entries; R = 2 implies max_len >= 9, so any 16 consecutive entries stay consecutive under the mask
-                for (uint32_t i = 16u * lane; i < Code<R>::kEntries; i += 16u * 64u) {
-                    const uint4 *v = reinterpret_cast<const uint4 *>(src + (i & mask));
-                    const uint4 x = v[0], y = v[1];
-                    uint4 sy, le;
-                    sy.x = __builtin_amdgcn_perm(x.y, x.x, 0x06040200u); le.x = __builtin_amdgcn_perm(x.y, x.x, 0x07050301u);
-                    sy.y = __builtin_amdgcn_perm(x.w, x.z, 0x06040200u); le.y = __builtin_amdgcn_perm(x.w, x.z, 0x07050301u);
-                    sy.z = __builtin_amdgcn_perm(y.y, y.x, 0x06040200u); le.z = __builtin_amdgcn_perm(y.y, y.x, 0x07050301u);
-                    sy.w = __builtin_amdgcn_perm(y.w, y.z, 0x06040200u); le.w = __builtin_amdgcn_perm(y.w, y.z, 0x07050301u);
-                    *reinterpret_cast<uint4 *>(sym_tab + i) = sy;
-                    *reinterpret_cast<uint4 *>(len_tab + i) = le;
-                }
-            }
-        }
-
-        if (n_held) {
-            uint4 *dst = reinterpret_cast<uint4 *>(words);
-            if (lane < n_held) dst[lane] = held_a;
-            if (lane + 64 < n_held) dst[lane + 64] = held_b;
-        }
-        // LDS written by some lanes of this wave is read by others: order the LDS accesses only
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-        if (!active) continue;
-
-        uint16_t *out_base = t.out + v0 + lane * 8u;
-
-        Decoder<R> dec;
-        dec.words = words; dec.last_word = P.stream_cap_words - 1u;
-        if (mode == ZM_MODE_CODED) {
-            // a6: this lane's bitstream has 8 * tiles + quantum * (its length byte) bits and starts where
-            // the bitstreams of the lanes below it end
-            const uint32_t units = reinterpret_cast<const uint8_t *>(words)[lane];
-            dec.start(wave_exclusive_sum(8u * tiles + quantum * units));
-        }
-
-        if (mode == ZM_MODE_CODED && full) {
-            // Common case, straight-line: a coded stream of whole groups of kGroup tiles (one group at the
-            // default stream length).  The first group's loads were issued above; from here on the wave only
-            // computes and stores, and asks for the next group's sign-mantissa bytes when a group is done.
-            const uint32_t groups = sn / (kGroup * kTile);
-            for (uint32_t q = 0;;) {
-#pragma unroll
-                for (int k = 0; k < kGroup; ++k)
-                    recover_and_store<kStreaming>(out_base + (q * kGroup + k) * kTile, dec.tile(len_tab, sym_tab), sm[k]);
-                if (++q == groups) break;
-#pragma unroll
-                for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (q * kGroup + k) * kTile);
+                const uint32_t nvec = min((o1 - o0) >> 4, P.stream_cap_words >> 2);
+                const uint4 *src = reinterpret_cast<const uint4 *>(t.echunks + at + o0);
+                uint4 *dst = reinterpret_cast<uint4 *>(words);
+                n_held = min(nvec, 128u);
+                if (lane < n_held) held_a = src[lane];
+                if (lane + 64 < n_held) held_b = src[lane + 64];
+                for (uint32_t i = 128 + lane; i < nvec; i += 64) dst[i] = src[i];
             }
         } else {
-            // General case: raw chunks, short last streams, streams that are not whole groups of kGroup tiles.
-            for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
-                if (g0) {
+            raw = t.echunks + at + static_cast<uint64_t>(s) * W;
+            if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.e_size) active = false;
+        }
+    }
+    // Next in the request order: the sign-mantissa bytes of the first kGroup tiles.  They stay in flight
+    // while the stream is staged and decoding starts.
+    uint2 sm[kGroup];
+    if (full) {
 #pragma unroll
-                    for (int k = 0; k < kGroup; ++k) {
-                        sm[k] = make_uint2(0u, 0u);
-                        if (g0 + k < tiles && mine - static_cast<int32_t>((g0 + k) * kTile) > 0)
-                            sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (g0 + k) * kTile);
-                    }
-                }
+        for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
+    } else {
+#pragma unroll
+        for (int k = 0; k < kGroup; ++k) {
+            sm[k] = make_uint2(0u, 0u);
+            if (static_cast<uint32_t>(k) < tiles && mine - static_cast<int32_t>(k * kTile) > 0)
+                sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
+        }
+    }
+
+    // a3: decode table -> LDS, its first 256 entries with the two bytes of an entry swapped (length low),
+    // replicated over the index bits above the longest code.  Four entries per lane, all loads issued before the
+    // first is used.  Every wave of the workgroup writes the same bytes (LDS word writes are atomic), so a wave may
+    // read as soon as its own writes are done: no workgroup barrier.
+    {
+        const uint16_t *src = reinterpret_cast<const uint16_t *>(t.lut);
+        const uint32_t mask = (1u << max_len) - 1u;
+        const uint32_t i = 4u * lane;
+        const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
+        const uint32_t ab = a | (b << 16), cd = c | (d << 16);
+        reinterpret_cast<uint2 *>(tab)[lane] = make_uint2(__builtin_amdgcn_perm(ab, ab, 0x02030001u), __builtin_amdgcn_perm(cd, cd, 0x02030001u));
+    }
+
+    if (n_held) {
+        uint4 *dst = reinterpret_cast<uint4 *>(words);
+        if (lane < n_held) dst[lane] = held_a;
+        if (lane + 64 < n_held) dst[lane + 64] = held_b;
+    }
+    // LDS written by some lanes of this wave is read by others: order the LDS accesses only
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+    if (!active) return;
+
+    uint16_t *out_base = t.out + v0 + lane * 8u;
+
+    const uint16_t *full_table = reinterpret_cast<const uint16_t *>(t.lut);
+    Decoder<R> dec;
+    dec.words = words; dec.last_word = P.stream_cap_words - 1u;
+    if (mode == ZM_MODE_CODED) {
+        // a6: this lane's bitstream has 8 * tiles + quantum * (its length byte) bits and starts where
+        // the bitstreams of the lanes below it end
+        const uint32_t units = reinterpret_cast<const uint8_t *>(words)[lane];
+        dec.start(wave_exclusive_sum(8u * tiles + quantum * units));
+    }
+
+    if (mode == ZM_MODE_CODED && full) {
+        // Common case, straight-line: a coded stream of whole groups of kGroup tiles (one group at the
+        // default stream length).  The first group's loads were issued above; from here on the wave only
+        // computes and stores, and asks for the next group's sign-mantissa bytes when a group is done.
+        const uint32_t groups = sn / (kGroup * kTile);
+        for (uint32_t q = 0;;) {
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k)
+                recover_and_store<kStreaming>(out_base + (q * kGroup + k) * kTile, dec.tile(tab, full_table, max_len), sm[k]);
+            if (++q == groups) break;
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (q * kGroup + k) * kTile);
+        }
+    } else {
+        // General case: raw chunks, short last streams, streams that are not whole groups of kGroup tiles.
+        for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
+            if (g0) {
 #pragma unroll
                 for (int k = 0; k < kGroup; ++k) {
-                    const uint32_t tile = g0 + k;
-                    if (tile < tiles) {
-                        const int32_t left = mine - static_cast<int32_t>(tile * kTile);
-                        uint2 ev = make_uint2(0u, 0u);
-                        if (mode == ZM_MODE_CODED) ev = dec.tile(len_tab, sym_tab);
-                        else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
-                        if (left >= 8) recover_and_store<kStreaming>(out_base + tile * kTile, ev, sm[k]);
-                        else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, sm[k], left);
-                    }
+                    sm[k] = make_uint2(0u, 0u);
+                    if (g0 + k < tiles && mine - static_cast<int32_t>((g0 + k) * kTile) > 0)
+                        sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (g0 + k) * kTile);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kGroup; ++k) {
+                const uint32_t tile = g0 + k;
+                if (tile < tiles) {
+                    const int32_t left = mine - static_cast<int32_t>(tile * kTile);
+                    uint2 ev = make_uint2(0u, 0u);
+                    if (mode == ZM_MODE_CODED) ev = dec.tile(tab, full_table, max_len);
+                    else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
+                    if (left >= 8) recover_and_store<kStreaming>(out_base + tile * kTile, ev, sm[k]);
+                    else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, sm[k], left);
                 }
             }
         }
-        // the next stream's bytes overwrite this one's in LDS: this wave's reads come first
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -421,31 +407,43 @@ template <int R, int kWaves, bool kStreaming>
 int launch_kernel(const Launch &L, uint32_t blocks, size_t lds, hipStream_t stream)
 {
     void *args[] = {const_cast<Launch *>(&L)};
-    const void *fn = L.streams_per_wave > 1 ? reinterpret_cast<const void *>(&zm_decode_kernel<R, kWaves, kStreaming, true>)
-                                            : reinterpret_cast<const void *>(&zm_decode_kernel<R, kWaves, kStreaming, false>);
+    const void *fn = reinterpret_cast<const void *>(&zm_decode_kernel<R, kWaves, kStreaming>);
     // the launch's own status: an error left behind by an earlier, unrelated call is not this call's
     return hipLaunchKernel(fn, dim3(blocks, L.n_tasks), dim3(64 * kWaves), args, lds, stream) == hipSuccess ? ZM_OK : ZM_E_HIP;
 }
 
+// Where the shapes of a call's launches go when they are asked for instead of launched.
+struct Recorder {
+    zm_launch_shape *out;
+    int cap;
+    int n = 0;
+};
+
 template <int R, int kWaves>
-int launch_tasks(Launch &L, size_t cap, hipStream_t stream)
+int launch_tasks(Launch &L, size_t cap, int stores, hipStream_t stream, Recorder *rec)
 {
     const size_t lds = 4 * kWaves * cap;                       // dynamic part: the streams
-    if (lds + 2 * Code<R>::kEntries > kLdsLimit) {
-        if constexpr (kWaves > 1) return launch_tasks<R, kWaves / 2>(L, cap, stream);
+    if (lds + 2 * kTableEntries > kLdsLimit) {
+        if constexpr (kWaves > 1) return launch_tasks<R, kWaves / 2>(L, cap, stores, stream, rec);
         else return ZM_E_ARG;                   // stream too long to stage in LDS
     }
     uint32_t blocks = 0;            // of the largest tensor; workgroups past a smaller tensor's end exit at once
     uint64_t out_bytes = 0;
     for (uint32_t k = 0; k < L.n_tasks; ++k) {
-        const uint32_t per_block = kWaves * L.streams_per_wave;
-        const uint32_t b = (L.task[k].n_streams + per_block - 1) / per_block;
+        const uint32_t b = (L.task[k].n_streams + kWaves - 1) / kWaves;
         blocks = b > blocks ? b : blocks;
         out_bytes += 2 * L.task[k].n_values;
     }
     if (!blocks) return ZM_OK;
-    return out_bytes > kLastLevelCacheBytes ? launch_kernel<R, kWaves, true>(L, blocks, lds, stream)
-                                            : launch_kernel<R, kWaves, false>(L, blocks, lds, stream);
+    const bool streaming = stores == ZM_STORES_STREAMING || (stores == ZM_STORES_AUTO && out_bytes > kLastLevelCacheBytes);
+    if (rec) {
+        if (rec->n < rec->cap)
+            rec->out[rec->n] = zm_launch_shape{static_cast<uint32_t>(R), static_cast<uint32_t>(kWaves), streaming ? 1u : 0u, blocks,
+                                               L.n_tasks, static_cast<uint32_t>(lds + 2 * kTableEntries)};
+        ++rec->n;
+        return ZM_OK;
+    }
+    return streaming ? launch_kernel<R, kWaves, true>(L, blocks, lds, stream) : launch_kernel<R, kWaves, false>(L, blocks, lds, stream);
 }
 
 // Collects the tensors of one round length and launches them, at most kMaxTasks per launch.
@@ -454,9 +452,11 @@ struct Group {
     static constexpr uint32_t kLenBound = R == 4 ? 8 : ZM_MAX_CODE_LEN;
     Launch L{};
     uint32_t max_stream = 0, max_quantum = 1;
+    int stores;
     hipStream_t stream;
+    Recorder *rec;
 
-    explicit Group(hipStream_t s) : stream(s) {}
+    Group(int store_policy, hipStream_t s, Recorder *r) : stores(store_policy), stream(s), rec(r) {}
 
     int add(const Task &t)
     {
@@ -471,12 +471,9 @@ struct Group {
         if (!L.n_tasks) return ZM_OK;
         const size_t cap = stream_cap_words(max_stream, kLenBound, max_quantum);
         L.stream_cap_words = static_cast<uint32_t>(cap);
-        L.streams_per_wave = 1;
-        // two streams per workgroup: measured on one MoE layer call of 118 MB, 1 / 2 / 4 / 8 waves per
-        // workgroup reach 63.1 / 63.2 / 61.9 / 58.2 % of the HBM roofline (1.2 GB calls: 72.5 / 72.9 / 73.2 / 72.0 %).
-        // With long codes a workgroup stages 8 KiB of tables, so four streams share them: 2 / 4 / 8 waves reach
-        // 41.9 / 45.6 / 45.6 % on a 170 MB call and 52.2 / 53.8 / 52.9 % on 1.2 GB calls.
-        const int rc = launch_tasks<R, R == 4 ? 2 : 4>(L, cap, stream);
+        // two streams per workgroup: on one MoE layer call of 118 MB one, two and four waves per workgroup are
+        // within 1 % of each other, eight are 5 % slower
+        const int rc = launch_tasks<R, 2>(L, cap, stores, stream, rec);
         L.n_tasks = 0; max_stream = 0; max_quantum = 1;
         return rc;
     }
@@ -518,16 +515,17 @@ constexpr int kMaxTensorsPerCall = 256;
 
 // Tensor i of a call, as make_task wants it; implemented by the two entry points.
 template <typename Describe>
-int decode_call(int n_tensors, Describe describe, hipStream_t stream)
+int decode_call(int n_tensors, Describe describe, int stores, hipStream_t stream, Recorder *rec = nullptr)
 {
+    if (stores != ZM_STORES_AUTO && stores != ZM_STORES_CACHED && stores != ZM_STORES_STREAMING) return ZM_E_ARG;
     // first pass: every tensor is checked before anything is launched
     for (int i = 0; i < n_tensors; ++i) {
         Task t; bool skip;
         const int rc = describe(i, t, skip);
         if (rc != ZM_OK) return rc;
     }
-    Group<4> short_codes(stream);
-    Group<2> long_codes(stream);
+    Group<4> short_codes(stores, stream, rec);
+    Group<2> long_codes(stores, stream, rec);
     for (int i = 0; i < n_tensors; ++i) {
         Task t; bool skip;
         describe(i, t, skip);
@@ -547,13 +545,27 @@ extern "C" int zm_decode_tensors(const zm_tensor_parts *parts, const zm_tensor_i
     if (n_tensors == 0) return ZM_OK;
     if (!parts || !infos || !out_bf16 || n_tensors < 0 || n_tensors > kMaxTensorsPerCall) return ZM_E_ARG;
     return decode_call(n_tensors, [&](int i, Task &t, bool &skip) { return make_task(parts[i], infos[i], out_bf16[i], t, skip); },
-                       static_cast<hipStream_t>(stream));
+                       ZM_STORES_AUTO, static_cast<hipStream_t>(stream));
 }
 
-extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_offsets,
-                                 const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
-                                 const int32_t *expert_ids, int n_selected,
-                                 void *const *out_bf16, void *stream)
+extern "C" int zm_decode_launch_shapes(const zm_tensor_info *infos, int n_tensors, int stores,
+                                       zm_launch_shape *shapes_out, int shapes_cap, int *n_shapes)
+{
+    if (!infos || n_tensors < 0 || n_tensors > kMaxTensorsPerCall || shapes_cap < 0 || (shapes_cap && !shapes_out) || !n_shapes) return ZM_E_ARG;
+    // the same path as a decode call, with placeholder addresses and a recorder in place of the launches
+    uint8_t *const somewhere = reinterpret_cast<uint8_t *>(uintptr_t{4096});
+    const zm_tensor_parts pt{somewhere, somewhere, somewhere, somewhere};
+    Recorder rec{shapes_out, shapes_cap};
+    const int rc = decode_call(n_tensors, [&](int i, Task &t, bool &skip) { return make_task(pt, infos[i], somewhere, t, skip); },
+                               stores, nullptr, &rec);
+    *n_shapes = rec.n;
+    return rc;
+}
+
+extern "C" int zm_decode_experts_stores(const void *const *blobs, const uint64_t *const *chunk_offsets,
+                                        const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
+                                        const int32_t *expert_ids, int n_selected,
+                                        void *const *out_bf16, int stores, void *stream)
 {
     if (n_selected == 0) return ZM_OK;
     if (!blobs || !chunk_offsets || !infos || !expert_ids || !out_bf16) return ZM_E_ARG;
@@ -572,7 +584,16 @@ extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const
         const zm_tensor_parts pt{blob + ti.lut_offset, chunk_offsets[src], blob + ti.sm_offset, blob + ti.e_offset};
         return make_task(pt, ti, out_bf16[i], t, skip);
     };
-    return decode_call(n_selected * tensors_per_expert, describe, static_cast<hipStream_t>(stream));
+    return decode_call(n_selected * tensors_per_expert, describe, stores, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int zm_decode_experts(const void *const *blobs, const uint64_t *const *chunk_offsets,
+                                 const zm_tensor_info *infos, int n_experts, int tensors_per_expert,
+                                 const int32_t *expert_ids, int n_selected,
+                                 void *const *out_bf16, void *stream)
+{
+    return zm_decode_experts_stores(blobs, chunk_offsets, infos, n_experts, tensors_per_expert, expert_ids, n_selected,
+                                    out_bf16, ZM_STORES_AUTO, stream);
 }
 
 extern "C" int zm_recover(const void *exponents, const void *sign_mantissa, size_t n_values, void *out_bf16, void *stream)

@@ -20,10 +20,11 @@ MAX_CODE_LEN = 12
 TILE_VALUES = 512
 MODE_CODED, MODE_RAW = 0, 1
 STAGING_BYTES = 32 << 20
+STORES_AUTO, STORES_CACHED, STORES_STREAMING = 0, 1, 2
 
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
-           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_tensors", "zm_decode_host_tensors",
-           "zm_decode_exponents_host", "zm_recover", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_image_bytes",
+           "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_experts_stores", "zm_decode_launch_shapes", "zm_decode_tensors", "zm_decode_host_tensors",
+           "zm_decode_exponents_host", "zm_recover", "zm_mover_probe", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_image_bytes",
            "zm_cache_pack_expert", "zm_cache_create",
            "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy", "zm_plan_selection_probabilities",
            "zm_plan_hit_distribution", "zm_plan_makespan", "zm_plan_expected_makespan", "zm_plan_pools",
@@ -44,6 +45,13 @@ class TensorParts(ctypes.Structure):
     """zm_tensor_parts"""
     _fields_ = [("table", ctypes.c_void_p), ("chunk_offsets", ctypes.c_void_p), ("sm", ctypes.c_void_p),
                 ("echunks", ctypes.c_void_p)]
+
+
+class LaunchShape(ctypes.Structure):
+    """zm_launch_shape"""
+    _fields_ = [("round_symbols", ctypes.c_uint32), ("waves_per_workgroup", ctypes.c_uint32),
+                ("streaming_stores", ctypes.c_uint32), ("workgroups", ctypes.c_uint32), ("tensors", ctypes.c_uint32),
+                ("lds_bytes", ctypes.c_uint32)]
 
 
 class CacheConfig(ctypes.Structure):
@@ -116,11 +124,17 @@ def lib() -> ctypes.CDLL:
         L.zm_decode_experts.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.POINTER(TensorInfo),
                                         c.c_int, c.c_int, c.POINTER(c.c_int32), c.c_int,
                                         c.POINTER(c.c_void_p), c.c_void_p]
+        L.zm_decode_experts_stores.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.POINTER(TensorInfo),
+                                               c.c_int, c.c_int, c.POINTER(c.c_int32), c.c_int,
+                                               c.POINTER(c.c_void_p), c.c_int, c.c_void_p]
+        L.zm_decode_launch_shapes.argtypes = [c.POINTER(TensorInfo), c.c_int, c.c_int, c.POINTER(LaunchShape), c.c_int,
+                                              c.POINTER(c.c_int)]
         L.zm_decode_tensors.argtypes = [c.POINTER(TensorParts), c.POINTER(TensorInfo), c.c_int,
                                         c.POINTER(c.c_void_p), c.c_void_p]
         L.zm_decode_host_tensors.argtypes = [c.POINTER(c.c_void_p), c.POINTER(TensorInfo), c.c_int,
                                              c.POINTER(c.c_void_p), c.c_void_p]
         L.zm_decode_exponents_host.argtypes = [c.c_void_p, c.c_size_t, c.c_uint32, c.c_uint32, u8p, c.c_int]
+        L.zm_mover_probe.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_size_t, c.c_int, c.c_int, c.c_void_p]
         L.zm_recover.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
         L.zm_cache_dispatch.argtypes = [u64p, c.c_int, c.POINTER(c.c_int32), c.c_int, c.c_int]
         L.zm_cache_arena_bytes.argtypes = [c.POINTER(CacheConfig), c.POINTER(TensorInfo), c.POINTER(c.c_size_t)]
@@ -260,9 +274,26 @@ def recover(exponents_ptr: int, sign_mantissa_ptr: int, n_values: int, out_ptr: 
                             ctypes.c_void_p(out_ptr), ctypes.c_void_p(stream)), "zm_recover")
 
 
+def mover_probe(src_ptr: int, dst_ptr: int, read_bytes: int, write_bytes: int, pieces_per_lane: int = 1,
+                streaming_stores: bool = False, stream: int = 0) -> None:
+    """zm_mover_probe on device pointers."""
+    _check(lib().zm_mover_probe(ctypes.c_void_p(src_ptr), ctypes.c_void_p(dst_ptr), read_bytes, write_bytes,
+                                pieces_per_lane, int(streaming_stores), ctypes.c_void_p(stream)), "zm_mover_probe")
+
+
 def decode_tensors(parts, infos, n_tensors: int, out_bf16, stream: int = 0) -> None:
     """zm_decode_tensors with ready-made ctypes arrays."""
     _check(lib().zm_decode_tensors(parts, infos, n_tensors, out_bf16, ctypes.c_void_p(stream)), "zm_decode_tensors")
+
+
+def decode_launch_shapes(infos: Sequence[TensorInfo], stores: int = 0) -> List[LaunchShape]:
+    """zm_decode_launch_shapes: the launches a decode call for these tensors would make."""
+    n = len(infos)
+    arr = (TensorInfo * max(1, n))(*infos)
+    out = (LaunchShape * 16)()
+    count = ctypes.c_int(0)
+    _check(lib().zm_decode_launch_shapes(arr, n, stores, out, 16, ctypes.byref(count)), "zm_decode_launch_shapes")
+    return list(out[: min(16, count.value)])
 
 
 def decode_host_tensors(host_blobs, infos, n_tensors: int, out_bf16, stream: int = 0) -> None:
@@ -326,7 +357,7 @@ class ExpertLayer:
         bufs = [torch.empty(at, dtype=torch.int16, device=self.device) for _ in range(n_selected)]
         return bufs, starts, vals
 
-    def make_call(self, expert_ids, out_buffers, starts):
+    def make_call(self, expert_ids, out_buffers, starts, stores: int = STORES_AUTO):
         """Pre-marshals one call: returns a zero-argument function that enqueues it on ``stream``."""
         ids = (ctypes.c_int32 * len(expert_ids))(*[int(e) for e in expert_ids])
         t = self.tensors_per_expert
@@ -334,18 +365,18 @@ class ExpertLayer:
         for j, buf in enumerate(out_buffers):
             for m in range(t):
                 outs[j * t + m] = buf.data_ptr() + 2 * starts[m]
-        f = lib().zm_decode_experts
-        args = (self._ptr_blobs, self._ptr_tables, self._ptr_infos, self.n_experts, t, ids, len(expert_ids), outs)
+        f = lib().zm_decode_experts_stores
+        args = (self._ptr_blobs, self._ptr_tables, self._ptr_infos, self.n_experts, t, ids, len(expert_ids), outs, stores)
 
         def call(stream: int = 0):
             rc = f(*args, ctypes.c_void_p(stream))
             if rc != OK:
-                raise ZipMoEError(rc, "zm_decode_experts")
+                raise ZipMoEError(rc, "zm_decode_experts_stores")
         call.keepalive = (ids, outs, out_buffers)
         return call
 
-    def decode(self, expert_ids, out_buffers, starts, stream: int = 0) -> None:
-        self.make_call(expert_ids, out_buffers, starts)(stream)
+    def decode(self, expert_ids, out_buffers, starts, stream: int = 0, stores: int = STORES_AUTO) -> None:
+        self.make_call(expert_ids, out_buffers, starts, stores)(stream)
 
 
 def cache_dispatch(counts, slots, tolerance: int, expert: int) -> int:

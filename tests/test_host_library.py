@@ -197,6 +197,51 @@ def test_decode_entry_points_refuse_bad_arguments_before_any_launch():
     assert L.zm_decode_experts((ctypes.c_void_p * 1)(good + 8), blobs, infos, 1, 1, ids, 1, outs, None) == zm.E_ARG
     assert L.zm_recover(None, ctypes.c_void_p(good), 8, ctypes.c_void_p(good), None) == zm.E_ARG
     assert L.zm_recover(ctypes.c_void_p(good), ctypes.c_void_p(good), 0, ctypes.c_void_p(good), None) == zm.OK
+    # the store policy of zm_decode_experts_stores is one of three values
+    assert L.zm_decode_experts_stores(blobs, blobs, infos, 1, 1, ids, 1, outs, 3, None) == zm.E_ARG
+    assert L.zm_decode_experts_stores(blobs, blobs, infos, 1, 1, ids, 1, outs, -1, None) == zm.E_ARG
+    assert L.zm_decode_experts_stores(blobs, blobs, infos, 1, 1, ids, 0, outs, zm.STORES_STREAMING, None) == zm.OK
+    # the lane quantum in the info must be the one the geometry defines
+    broken = zm.TensorInfo.from_buffer_copy(info)
+    broken.lane_quantum += 1
+    assert L.zm_decode_tensors(parts, (zm.TensorInfo * 1)(broken), 1, outs, None) == zm.E_ARG
+    # the staged and the probe entry points check their arguments on the host as well
+    host = (ctypes.c_void_p * 1)(blob.ctypes.data)
+    assert L.zm_decode_host_tensors(host, infos, 0, outs, None) == zm.OK
+    assert L.zm_decode_host_tensors(None, infos, 1, outs, None) == zm.E_ARG
+    assert L.zm_decode_host_tensors(host, infos, 257, outs, None) == zm.E_ARG
+    huge = zm.TensorInfo.from_buffer_copy(info)
+    huge.blob_size = (zm.STAGING_BYTES + 256)
+    assert L.zm_decode_host_tensors(host, (zm.TensorInfo * 1)(huge), 1, outs, None) == zm.E_SIZE
+    assert L.zm_mover_probe(None, ctypes.c_void_p(good), 16, 16, 1, 0, None) == zm.E_ARG
+    assert L.zm_mover_probe(ctypes.c_void_p(good), ctypes.c_void_p(good), 24, 16, 1, 0, None) == zm.E_ARG
+    assert L.zm_mover_probe(ctypes.c_void_p(good), ctypes.c_void_p(good), 16, 16, 3, 0, None) == zm.E_ARG
+
+
+def test_launch_shapes_follow_code_length_stream_length_and_output_size():
+    """zm_decode_launch_shapes is host logic: the same rule the decode calls launch by"""
+    def info_of(kind, n, C, W, max_len):
+        return zm.blob_info(zm.compress(synth.special_tensor(kind, n, 3), C, W, max_len)[0][:384])
+
+    short, long_ = info_of("gauss", 50000, 16384, 4096, 8), info_of("wide", 50000, 16384, 4096, 12)
+    assert short.max_len <= 8 < long_.max_len
+    shapes = zm.decode_launch_shapes([short, long_, short])
+    assert [(s.round_symbols, s.waves_per_workgroup, s.streaming_stores, s.tensors) for s in shapes] == [(4, 2, 0, 2), (2, 2, 0, 1)]
+    assert shapes[0].workgroups == -(-(-(-50000 // 4096)) // 2) and shapes[0].lds_bytes < 10 * 1024
+    assert all(s.streaming_stores == 1 for s in zm.decode_launch_shapes([short, long_], zm.STORES_STREAMING))
+    # more than 48 tensors of a kind are split over launches
+    assert [s.tensors for s in zm.decode_launch_shapes([short] * 100)] == [48, 48, 4]
+    # streams too long for two of them to share a workgroup's LDS get a workgroup each
+    wide_stream = info_of("gauss", 70000, 32768, 32768, 8)
+    assert [(s.round_symbols, s.waves_per_workgroup) for s in zm.decode_launch_shapes([wide_stream])] == [(4, 1)]
+    # a call that writes more than 256 MB streams its stores when the policy is left to the library
+    big = zm.TensorInfo.from_buffer_copy(short)
+    big.n_values = 140 << 20
+    big.e_offset = big.sm_offset + (big.n_values + 255) // 256 * 256
+    big.blob_size = big.e_offset + 256
+    big.n_chunks = -(-big.n_values // big.chunk_values)
+    assert [s.streaming_stores for s in zm.decode_launch_shapes([big])] == [1]
+    assert [s.streaming_stores for s in zm.decode_launch_shapes([big], zm.STORES_CACHED)] == [0]
 
 
 def test_cache_configuration_is_checked_on_the_host():
