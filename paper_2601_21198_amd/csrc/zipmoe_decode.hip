@@ -263,12 +263,19 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
             if (mode != ZM_MODE_RAW || at + static_cast<uint64_t>(s) * W + ((sn + 15u) & ~15u) > t.e_size) active = false;
         }
     }
-    // Next in the request order: the sign-mantissa bytes of the first kGroup tiles.  They stay in flight
-    // while the stream is staged and decoding starts.
+    // Next in the request order: the sign-mantissa bytes of the first tiles.  They stay in flight while the
+    // stream is staged and decoding starts.  With ordinary stores a straight-line stream asks for its first
+    // kAhead tiles here and for tile k + kAhead when tile k is done: the requests of the thousands of waves that
+    // start together are spread out, everyone's first tile arrives sooner (one layer call of 118 MB: 64.5 -> 70 %
+    // of the roofline with cache-resident outputs, 56 -> 58.5 % with cold ones).  A wave waits for such a later
+    // load behind its own earlier stores, though, and non-temporal stores take long to be acknowledged: with
+    // them all eight tiles are asked for up front (rolling requests there: between -4 % and +3 %).
+    constexpr int kAhead = kStreaming ? kGroup : 4;
+    const bool straight = full && mode == ZM_MODE_CODED;
     uint2 sm[kGroup];
-    if (full) {
+    if (straight) {
 #pragma unroll
-        for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
+        for (int k = 0; k < kAhead; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
     } else {
 #pragma unroll
         for (int k = 0; k < kGroup; ++k) {
@@ -314,15 +321,18 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         dec.start(wave_exclusive_sum(8u * tiles + quantum * units));
     }
 
-    if (mode == ZM_MODE_CODED && full) {
+    if (straight) {
         // Common case, straight-line: a coded stream of whole groups of kGroup tiles (one group at the
-        // default stream length).  The first group's loads were issued above; from here on the wave only
-        // computes and stores, and asks for the next group's sign-mantissa bytes when a group is done.
+        // default stream length).  The first group's loads were issued above (the rest of them follow tile by
+        // tile); from here on the wave only computes and stores, and asks for the next group's sign-mantissa
+        // bytes when a group is done.
         const uint32_t groups = sn / (kGroup * kTile);
         for (uint32_t q = 0;;) {
 #pragma unroll
-            for (int k = 0; k < kGroup; ++k)
+            for (int k = 0; k < kGroup; ++k) {
                 recover_and_store<kStreaming>(out_base + (q * kGroup + k) * kTile, dec.tile(tab, full_table, max_len), sm[k]);
+                if (q == 0 && k + kAhead < kGroup) sm[k + kAhead] = *reinterpret_cast<const uint2 *>(sm_base + (k + kAhead) * kTile);
+            }
             if (++q == groups) break;
 #pragma unroll
             for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (q * kGroup + k) * kTile);
