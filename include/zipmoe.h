@@ -119,8 +119,9 @@ int zm_exponent_histogram(const uint16_t *bf16, size_t n_values, uint64_t hist[2
  * symbols, else ZM_E_ARG. */
 int zm_build_codebook(const uint64_t hist[256], int max_len, uint8_t code_len_out[256]);
 
-/* Upper bound on the blob size zm_encode can produce. 0 if the geometry is
- * not admissible (see zm_encode). */
+/* Upper bound on the size of the serialised object of Sec. 3.1 (all components plus their
+ * metadata in one binary object) that zm_encode can produce for a tensor of n_values. 0 if the
+ * geometry is not admissible (see zm_encode). */
 size_t zm_encode_bound(size_t n_values, uint32_t chunk_values, uint32_t stream_values);
 
 /* Offline initialisation of one tensor (Sec. 3.1): split, shard, encode, pack,
@@ -145,14 +146,15 @@ int zm_encode(const uint16_t *bf16, size_t n_values, uint32_t chunk_values, uint
               const uint8_t code_len[256], uint8_t *blob, size_t blob_cap, size_t *blob_size,
               uint64_t *chunk_offsets, size_t chunk_offsets_cap, size_t *n_chunks);
 
-/* Reads and checks the header and codebook of a blob in host memory (size may
- * be just the first 384 bytes or the whole blob) and fills *info.
+/* The metadata that Sec. 3.1 serialises with the compressed components: reads and
+ * checks the header and codebook of a blob in host memory (size may be just the first
+ * 384 bytes or the whole blob) and fills *info.
  * ZM_E_FORMAT if magic, version, geometry, section offsets or codebook are
  * not consistent. */
 int zm_blob_info(const void *blob_host, size_t size, zm_tensor_info *info);
 
-/* Full structural check of a blob in host memory, to be run once when a blob
- * is registered, before it is uploaded: header, codebook, decode table against
+/* Full structural check of a serialised tensor (the binary object of Sec. 3.1) in host
+ * memory, to be run once when a blob is registered, before it is uploaded: header, codebook, decode table against
  * the codebook, chunk table, every chunk header and stream offset, every
  * address a decoder will touch inside blob_size.  ZM_E_FORMAT on any
  * violation.  It does not decode the streams. */

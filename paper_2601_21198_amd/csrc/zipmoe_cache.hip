@@ -133,6 +133,12 @@ struct zm_cache {
     hipStream_t copy_stream = nullptr;
     hipEvent_t ev_start = nullptr, ev_copied = nullptr;
     bool broken = false;                       // a fetch failed half-way: slots and bookkeeping may disagree
+    // work lists of a fetch (sized at creation for max_selected experts; a fetch is not re-entrant anyway)
+    struct Plan { int expert, found, target, slot; };
+    std::vector<Plan> plan;
+    std::vector<zm_tensor_parts> parts_now, parts_later;
+    std::vector<zm_tensor_info> infos_now, infos_later;
+    std::vector<void *> out_now, out_later;
 
     uint8_t *slot_ptr(int pool, int slot) const { return arena + lay.pool_off[pool] + lay.slot_bytes[pool] * static_cast<size_t>(slot); }
     uint8_t *transient_ptr(int j) const { return arena + lay.transient_off + lay.transient_bytes * static_cast<size_t>(j); }
@@ -212,6 +218,11 @@ int zm_cache_create(const zm_cache_config *config, const void *const *host_blobs
         }
         c->arena = static_cast<uint8_t *>(arena);
         c->count.assign(config->n_experts, 0);
+        const size_t most = static_cast<size_t>(config->max_selected) * config->tensors_per_expert;
+        c->plan.resize(config->max_selected);
+        c->parts_now.resize(most); c->parts_later.resize(most);
+        c->infos_now.resize(most); c->infos_later.resize(most);
+        c->out_now.resize(most); c->out_later.resize(most);
         c->pool_of.assign(config->n_experts, static_cast<int8_t>(kUncached));
         c->slot_of.assign(config->n_experts, -1);
         for (int p = 0; p < kPools; ++p) c->owner[p].assign(config->slots[p], -1);
@@ -278,8 +289,8 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
 
     for (int j = 0; j < n_selected; ++j) ++c->count[expert_ids[j]];
 
-    struct Plan { int expert, found, target, slot; };
-    Plan plan[256];
+    using Plan = zm_cache::Plan;
+    Plan *plan = c->plan.data();
     auto selected = [&](int e) { for (int j = 0; j < n_selected; ++j) if (expert_ids[j] == e) return true; return false; };
     for (int j = 0; j < n_selected; ++j) {
         const int e = expert_ids[j];
@@ -319,9 +330,9 @@ int zm_cache_fetch(zm_cache *c, const int32_t *expert_ids, int n_selected, void 
     }
 
     // data movement and decode lists
-    zm_tensor_parts parts_now[256], parts_later[256];
-    zm_tensor_info infos_now[256], infos_later[256];
-    void *out_now[256], *out_later[256];
+    zm_tensor_parts *parts_now = c->parts_now.data(), *parts_later = c->parts_later.data();
+    zm_tensor_info *infos_now = c->infos_now.data(), *infos_later = c->infos_later.data();
+    void **out_now = c->out_now.data(), **out_later = c->out_later.data();
     int n_now = 0, n_later = 0;
     bool any_copy = false;
     for (int j = 0; j < n_selected; ++j) {

@@ -300,7 +300,7 @@ int decode_chunk_exponents(const uint8_t *p, const zm_tensor_info &t, const uint
 
 extern "C" {
 
-int zm_version(void) { return 100; }
+int zm_version(void) { return 20000; }    // 2.0.0: serialised format 3
 
 const char *zm_strerror(int status)
 {

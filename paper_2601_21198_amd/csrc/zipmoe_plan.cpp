@@ -12,11 +12,15 @@
 
 namespace {
 
-// coefficients 0..deg of prod_i (1 + w_i x) over i in [lo, hi), truncated at degree deg
-void poly_times(std::vector<double> &p, double w, int deg)
+// p(x) *= (a + b x), coefficients above degree deg dropped
+void poly_times(std::vector<double> &p, double a, double b, int deg)
 {
-    for (int j = deg; j >= 1; --j) p[j] += w * p[j - 1];
+    for (int j = deg; j >= 1; --j) p[j] = a * p[j] + b * p[j - 1];
+    p[0] *= a;
 }
+
+// p(x) *= (1 + w x): the generating polynomial of the weights' elementary symmetric polynomials (App. D)
+void poly_times(std::vector<double> &p, double w, int deg) { poly_times(p, 1.0, w, deg); }
 
 // f_i implied by the weights: w_i * R(k-1, all but i) / R(k, all), with the leave-one-out symmetric
 // polynomials taken from prefix and suffix products (no division).
@@ -39,24 +43,33 @@ void implied_inclusion(const std::vector<double> &w, int k, std::vector<double> 
     }
 }
 
+// App. C: the number of selected ranks among n independent draws with probabilities q has the generating
+// polynomial prod_r ((1 - q_r) + q_r x); phi[h] is its coefficient of x^h.
 void hit_distribution(const double *q, int n, double *phi)
 {
-    for (int h = 0; h <= n; ++h) phi[h] = 0.0;
-    phi[0] = 1.0;
-    for (int r = 0; r < n; ++r) {
-        for (int h = std::min(r + 1, n); h >= 1; --h) phi[h] = phi[h] * (1.0 - q[r]) + phi[h - 1] * q[r];
-        phi[0] *= 1.0 - q[r];
-    }
+    std::vector<double> poly(n + 1, 0.0);
+    poly[0] = 1.0;
+    for (int r = 0; r < n; ++r) poly_times(poly, 1.0 - q[r], q[r], std::min(r + 1, n));
+    std::copy(poly.begin(), poly.end(), phi);
 }
 
-double makespan(int k, const int32_t h[4], const zm_plan_costs &p)
+// What an expert found in each state still needs (App. C; Sec. 3.2): {SM-chunks read, E-chunks read, decompression}.
+// States: the pools F, C, S, E and, last, cached nowhere.
+constexpr int kNeeds[5][3] = {{0, 0, 0}, {0, 0, 1}, {0, 1, 1}, {1, 0, 1}, {1, 1, 1}};
+
+// App. C: the I/O thread reads everything that is missing one after the other; the L workers share the E-chunk
+// reads they wait for and the decompressions; the layer takes the longer of the two.
+double makespan(int k, const int32_t hits[4], const zm_plan_costs &p)
 {
-    const double n_sm = static_cast<double>(p.tensors_per_expert) * (k - h[0] - h[1] - h[2]);
-    const double n_e = static_cast<double>(p.tensors_per_expert) * p.shards_per_tensor * (k - h[0] - h[1] - h[3]);
-    const double n_d = static_cast<double>(p.tensors_per_expert) * p.shards_per_tensor * (k - h[0]);
-    const double t_io = n_sm * p.sm_read_delay + n_e * p.e_read_delay;
-    const double t_decomp = (n_e * p.e_read_delay + n_d * p.decompress_delay) / p.threads;
-    return std::max(t_io, t_decomp);
+    int in_state[5] = {hits[0], hits[1], hits[2], hits[3], k - hits[0] - hits[1] - hits[2] - hits[3]};
+    double experts[3] = {0.0, 0.0, 0.0};                   // experts that need each of the three things
+    for (int s = 0; s < 5; ++s)
+        for (int part = 0; part < 3; ++part) experts[part] += in_state[s] * kNeeds[s][part];
+    const double tensors = p.tensors_per_expert, shards = tensors * p.shards_per_tensor;
+    const double sm_reads = experts[0] * tensors * p.sm_read_delay;
+    const double e_reads = experts[1] * shards * p.e_read_delay;
+    const double decompressions = experts[2] * shards * p.decompress_delay;
+    return std::max(sm_reads + e_reads, (e_reads + decompressions) / p.threads);
 }
 
 bool costs_ok(const zm_plan_costs *p)
@@ -116,7 +129,9 @@ int zm_plan_selection_probabilities(const double *f, int n, int k, int max_iters
 int zm_plan_hit_distribution(const double *q, int n, double *phi_out)
 {
     if ((!q && n > 0) || !phi_out || n < 0) return ZM_E_ARG;
-    hit_distribution(q, n, phi_out);
+    try {
+        hit_distribution(q, n, phi_out);
+    } catch (const std::bad_alloc &) { return ZM_E_NOMEM; }
     return ZM_OK;
 }
 
