@@ -242,25 +242,28 @@ bool unpack_stream(const uint8_t *stream, size_t n_bytes, uint32_t n, const uint
     const uint32_t mask = (1u << max_len) - 1u;
     if (n_bytes < kLanes) return false;
     const uint8_t *payload = stream + kLanes;
-    const uint64_t payload_bits = (n_bytes - kLanes) * 8ull;
-    auto window = [&](uint64_t bit) {                    // the 32 bits from `bit` on (zeros past the end)
-        uint64_t w = 0;
-        const uint64_t byte = bit >> 3;
-        for (uint32_t k = 0; k < 5 && byte + k < n_bytes - kLanes; ++k) w |= static_cast<uint64_t>(payload[byte + k]) << (8 * k);
-        return static_cast<uint32_t>(w >> (bit & 7));
-    };
+    const size_t payload_words = (n_bytes - kLanes) / 4;
+    const uint64_t payload_bits = payload_words * 32ull;
+    auto word = [&](size_t i) -> uint64_t { return i < payload_words ? load_le<uint32_t>(payload + 4 * i) : 0u; };   // zeros past the end
     uint64_t start = 0;
     for (uint32_t lane = 0; lane < kLanes; ++lane) {
         const uint64_t span = syms + static_cast<uint64_t>(quantum) * stream[lane];
         if (start + span > payload_bits) return false;
-        uint64_t bit = start;
+        // a 64-bit buffer over the lane's bitstream, topped up a word at a time: at least 32 valid bits before a lookup
+        size_t next = start >> 5;
+        uint64_t buffer = (word(next) | word(next + 1) << 32) >> (start & 31);
+        uint32_t valid = 64 - static_cast<uint32_t>(start & 31);
+        next += 2;
+        uint64_t used = 0;
         for (uint32_t j = 0; j < syms; ++j) {
-            const uint32_t x = window(bit) & mask;
+            const uint32_t x = static_cast<uint32_t>(buffer) & mask;
             const uint32_t idx = (j / kRun) * kTile + lane * kRun + (j % kRun);
             if (idx < n) e[idx] = lut[2 * x];
-            bit += lut[2 * x + 1];
+            const uint32_t len = lut[2 * x + 1];
+            buffer >>= len; valid -= len; used += len;
+            if (valid <= 32) { buffer |= word(next++) << valid; valid += 32; }
         }
-        if (bit > start + span) return false;
+        if (used > span) return false;
         start += span;
     }
     return true;
