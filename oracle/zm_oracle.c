@@ -39,7 +39,7 @@
 /* ---- layout constants of the serialised object ------------------------- */
 
 #define ZO_MAGIC        0x454F4D5Au   /* bytes 'Z','M','O','E' */
-#define ZO_VERSION      3u
+#define ZO_VERSION      4u
 #define ZO_HEADER_BYTES 128u
 #define ZO_LANES        64u   /* per-stream lanes                              */
 #define ZO_RUN          8u    /* consecutive values one lane owns in a tile     */
@@ -212,15 +212,21 @@ static int pad_symbol(const uint8_t len[256])
  * taken tile after tile.  Positions at or past the stream's end hold the pad
  * symbol.
  *
- * Each lane has a bitstream of its own: the codes of its symbols one after
- * the other, the first bit of a code first.  With m = 8*tiles symbols and T
- * code bits, the lane's bitstream is given D = m + q*b bits in the stream,
- * where q (the "quantum", a constant of the tensor kept in the header) and
- * the byte b = ceil((T - m) / q) make D the smallest such number >= T; the
- * D - T bits after the last code are zero.  (Every code has at least one
- * bit, so T >= m; q is the smallest integer >= 1 for which b fits a byte
- * whatever the symbols are: q >= (L - 1) * (W / 64) / 255, L the longest
- * code of the book, W the stream length of the tensor.)
+ * Each lane has a bitstream of its own, D = m + q*b bits long (m = 8*tiles
+ * symbols, T code bits, q the "quantum", a constant of the tensor kept in the
+ * header, and the byte b = ceil((T - m) / q), which makes D the smallest such
+ * number >= T).  It is filled from both ends, so that a decoder can work on
+ * two independent halves at once:
+ *   - the codes of the lane's first m/2 symbols, in order, from the lane's
+ *     first bit upwards, the first bit of a code first;
+ *   - the codes of its last m/2 symbols, in reverse order (symbol m-1 first),
+ *     from the lane's last bit downwards, the first bit of a code at the
+ *     higher position;
+ *   - the D - T bits left in the middle are zero.
+ * (Every code has at least one bit, so T >= m; q is the smallest integer
+ * >= 1 for which b fits a byte whatever the symbols are:
+ * q >= (L - 1) * (W / 64) / 255, L the longest code of the book, W the stream
+ * length of the tensor.)
  *
  * The stream is
  *   bytes 0..63   b of lane 0, lane 1, ..., lane 63
@@ -229,8 +235,8 @@ static int pad_symbol(const uint8_t len[256])
  *                 Bit k of this payload is bit (k mod 32) of its 32-bit
  *                 little-endian word k / 32, i.e. bit (k mod 8) of byte k / 8.
  *   then          zero bits up to a multiple of 16 bytes.
- * A decoder finds every lane's first bit with a prefix sum over the 64 bytes
- * and then reads each lane's bits independently of the others.
+ * A decoder finds every lane's first and last bit with a prefix sum over the
+ * 64 bytes and then reads each lane's bits independently of the others.
  */
 
 /* the quantum q of a tensor whose longest code has L bits and whose streams
@@ -248,6 +254,13 @@ static size_t stream_bytes_bound(uint32_t stream_values)
     size_t tiles = (stream_values + ZO_TILE - 1) / ZO_TILE;
     size_t bits = (size_t)ZO_LANES * (tiles * ZO_RUN * ZO_MAX_LEN + 255);   /* code bits + rounding to the quantum */
     return round_up(ZO_LANES + (bits + 7) / 8, 16);
+}
+
+/* symbol number j of a lane: value i = j mod 8 of the lane's run in tile j / 8 */
+static int lane_symbol(const uint8_t *e, uint32_t n, int pad, uint32_t lane, uint32_t j)
+{
+    uint32_t idx = (j / ZO_RUN) * ZO_TILE + lane * ZO_RUN + (j % ZO_RUN);
+    return idx < n ? e[idx] : pad;
 }
 
 static void put_bit(uint8_t *payload, uint64_t k, uint32_t bit)
@@ -270,17 +283,27 @@ static size_t encode_stream(const uint8_t *e, uint32_t n, const uint8_t len[256]
     uint8_t *payload = out + ZO_LANES;
     uint64_t at = 0;                             /* payload bit where the current lane starts */
     for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
+        /* the lane's symbols in decode order, and its code bits */
+        uint32_t T = 0;
+        for (uint32_t j = 0; j < m; j++) T += len[lane_symbol(e, n, pad, lane, j)];
+        uint32_t units = (T - m + q - 1) / q;                /* at most 255 by the choice of q */
+        uint64_t D = m + (uint64_t)q * units;
+        out[lane] = (uint8_t)units;
+        /* first half: upwards from the lane's first bit */
         uint64_t k = at;
-        for (uint32_t j = 0; j < m; j++) {
-            uint32_t idx = (j / ZO_RUN) * ZO_TILE + lane * ZO_RUN + (j % ZO_RUN);
-            int s = idx < n ? e[idx] : pad;
+        for (uint32_t j = 0; j < m / 2; j++) {
+            int s = lane_symbol(e, n, pad, lane, j);
             for (int b = len[s] - 1; b >= 0; b--)            /* first wire bit = top bit of the code */
                 put_bit(payload, k++, (code[s] >> b) & 1u);
         }
-        uint32_t T = (uint32_t)(k - at);
-        uint32_t units = (T - m + q - 1) / q;                /* at most 255 by the choice of q */
-        out[lane] = (uint8_t)units;
-        at += m + (uint64_t)q * units;
+        /* second half, last symbol first: downwards from the lane's last bit */
+        k = at + D;
+        for (uint32_t j = m; j-- > m / 2; ) {
+            int s = lane_symbol(e, n, pad, lane, j);
+            for (int b = len[s] - 1; b >= 0; b--)
+                put_bit(payload, --k, (code[s] >> b) & 1u);
+        }
+        at += D;
     }
     return round_up(ZO_LANES + (at + 7) / 8, 16);
 }
@@ -305,14 +328,17 @@ static int decode_stream(const uint8_t *stream, size_t n_bytes, uint32_t n,
     for (uint32_t lane = 0; lane < ZO_LANES; lane++) {
         const uint64_t D = m + (uint64_t)q * stream[lane];
         if (at + D > payload_bits) return ZO_E_FORMAT;
-        uint64_t k = at;
-        for (uint32_t j = 0; j < m; j++) {
+        /* lo: next bit of the first half (moving up); hi: one past the next bit of the second half (moving down) */
+        uint64_t lo = at, hi = at + D;
+        for (uint32_t step = 0; step < m; step++) {
+            const int up = step < m / 2;
+            const uint32_t j = up ? step : m - 1 - (step - m / 2);
             /* walk the code one bit at a time until it equals a code of the book */
             uint32_t acc = 0; int l = 0, found = -1;
             while (found < 0 && l < L) {
-                if (k >= at + D) return ZO_E_FORMAT;
-                acc = (acc << 1) | get_bit(payload, k);
-                k++; l++;
+                if (lo >= hi) return ZO_E_FORMAT;             /* the two halves may not run into each other */
+                acc = (acc << 1) | get_bit(payload, up ? lo++ : --hi);
+                l++;
                 for (int s = 0; s < 256; s++)
                     if (len[s] == l && code[s] == acc) { found = s; break; }
             }
@@ -321,8 +347,8 @@ static int decode_stream(const uint8_t *stream, size_t n_bytes, uint32_t n,
             if (idx < n) e[idx] = (uint8_t)found;
             else if (found != pad) return ZO_E_FORMAT;
         }
-        if (at + D - k >= q) return ZO_E_FORMAT;             /* a smaller byte would have done */
-        for (; k < at + D; k++) if (get_bit(payload, k)) return ZO_E_FORMAT;
+        if (hi - lo >= q) return ZO_E_FORMAT;                /* a smaller byte would have done */
+        for (uint64_t k = lo; k < hi; k++) if (get_bit(payload, k)) return ZO_E_FORMAT;
         at += D;
     }
     if (n_bytes != round_up(ZO_LANES + (at + 7) / 8, 16)) return ZO_E_FORMAT;

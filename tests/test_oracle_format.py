@@ -121,8 +121,9 @@ def test_stream_sizes_match_closed_form(max_len, W):
 
 @pytest.mark.parametrize("kind,n,W,max_len", [("gauss", 4096, 4096, 8), ("wide", 3000, 4096, 12), ("gauss", 700, 1024, 8)])
 def test_every_lane_decodes_by_hand_from_its_prefix_sum_position(kind, n, W, max_len):
-    """an independent decoder written from the format's definition: lane j starts at the sum of the bit
-    counts of lanes 0..j-1 (64 + q*byte each... m + q*byte), its codes follow bit by bit, first code bit first"""
+    """an independent decoder written from the format's definition: lane j's bits start at the sum of the bit
+    counts (m + q*byte) of lanes 0..j-1; its first m/2 symbols are read upwards from its first bit, its last
+    m/2 symbols, last one first, downwards from its last bit, the first bit of a code first either way"""
     w = synth.special_tensor(kind, n, seed=1)
     blob, lengths = roundtrip(w, W, W, max_len)
     code, _ = zo.canonical(lengths)
@@ -134,18 +135,32 @@ def test_every_lane_decodes_by_hand_from_its_prefix_sum_position(kind, n, W, max
     e, _ = zo.split(w)
     per_lane, pad = lane_symbols(e, lengths)
     m, q = per_lane.shape[1], h["quantum"]
+
+    def read_code(next_bit):
+        acc, l = 0, 0
+        while (l, acc) not in book:
+            acc = (acc << 1) | int(bits[next_bit()])
+            l += 1
+        return book[(l, acc)]
+
     start = 0
     for lane in range(64):
-        k = start
-        for j in range(m):
-            acc, l = 0, 0
-            while (l, acc) not in book:
-                acc = (acc << 1) | int(bits[k])
-                k += 1
-                l += 1
-            assert book[(l, acc)] == per_lane[lane, j]
         D = m + q * int(stream[lane])
-        assert k <= start + D < k + q and not bits[k: start + D].any()
+        up, down = [start], [start + D]
+
+        def upwards():
+            up[0] += 1
+            return up[0] - 1
+
+        def downwards():
+            down[0] -= 1
+            return down[0]
+
+        for j in range(m // 2):
+            assert read_code(upwards) == per_lane[lane, j]
+        for j in range(m - 1, m // 2 - 1, -1):
+            assert read_code(downwards) == per_lane[lane, j]
+        assert 0 <= down[0] - up[0] < q and not bits[up[0]: down[0]].any()      # what is left in the middle is zero
         start += D
     assert not bits[start:].any() and stream.size == -(-(64 + -(-start // 8)) // 16) * 16
 
