@@ -20,12 +20,16 @@
 //   2. the sign-mantissa bytes of the stream's first eight tiles are requested;
 //   3. the decode table goes to LDS (a3) as two byte tables (code length, symbol)
 //      at fixed LDS addresses, replicated to the full index width;
-//   4. a wavefront prefix sum over the 64 lane-length bytes gives every lane the first bit of its own
-//      bitstream (a6): what varies from lane to lane is where its input lies, its output positions are fixed;
-//   5. lock-step decode (a5): every lane keeps two words (lo, hi) of its bitstream, a bit position and the
-//      index of its next word; per round it extracts a 32-bit window with one funnel shift and decodes R
-//      symbols by table lookup; the next word is requested at the start of the round, so that a lane that
-//      crosses a word boundary finds it there;
+//   4. a wavefront prefix sum over the 64 lane-length bytes gives every lane the first and the last bit of
+//      its own bitstream (a6): what varies from lane to lane is where its input lies, its output positions
+//      are fixed;
+//   5. lock-step decode (a5): a lane's bitstream holds the first half of its symbols from its first bit upwards
+//      and the second half, last symbol first, from its last bit downwards, so every lane runs two independent
+//      decode chains at once (the lookups of one overlap the latency of the other).  Per chain it keeps two
+//      words of the bitstream, a bit position and the index of its next word; per round it extracts a 32-bit
+//      window with one funnel shift (bit-reversed for the downward chain) and decodes R symbols by table
+//      lookup; the next word is requested at the start of the round, so that a chain that crosses a word
+//      boundary finds it there;
 //   6. the eight decoded exponent bytes are merged with the sign-mantissa bytes
 //      by byte-parallel bit operations and stored (a8).
 #include <hip/hip_runtime.h>
@@ -125,7 +129,9 @@ __device__ __forceinline__ void recover_and_store_partial(uint16_t *dst, uint2 e
 
 constexpr uint32_t kTableEntries = 256;   // the LDS table resolves the first eight bits of a code
 
-// Lock-step decoder state of one lane (a5).
+// Lock-step decoder state of one lane (a5): two chains, one reading the lane's bitstream upwards from its
+// first bit (the first half of the lane's symbols, in order), one reading it downwards from its last bit (the
+// second half, last symbol first).
 // R = 4: every code has at most 8 bits, four symbols per 32-bit window.  R = 2: codes of up to ZM_MAX_CODE_LEN
 // bits, two symbols per window; the LDS table still resolves eight bits, and a lane that meets a longer code
 // (its table entry carries a length above 8: no code of at most 8 bits begins with these bits) takes its entry
@@ -134,64 +140,98 @@ template <int R>
 struct Decoder {
     const uint32_t *words;        // the stream as staged in LDS (length bytes included)
     uint32_t last_word;           // highest index a read may use
-    uint32_t lo = 0, hi = 0;      // words q and q+1 of this lane's bitstream
-    uint32_t pos = 0;             // bits of lo already used (< 32 at the start of a round)
-    uint32_t next = 0;            // index of word q+2
+    // upward chain: words q and q+1 of the bitstream, bits of lo already used (< 32 at the start of a round), index of word q+2
+    uint32_t lo = 0, hi = 0, pos = 0, next = 0;
+    // downward chain: dhi is the word that holds the bits just below the read position, of which its low dpos
+    // bits (0..31) are still unread, dlo the word below it, dnext the index of the word below that
+    uint32_t dlo = 0, dhi = 0, dpos = 0, dnext = 0;
 
-    // first_bit: where this lane's bitstream starts, counted from the first payload bit
-    __device__ __forceinline__ void start(uint32_t first_bit)
+    // first_bit, end_bit: where this lane's bitstream starts and ends, counted from the first payload bit
+    __device__ __forceinline__ void start(uint32_t first_bit, uint32_t end_bit)
     {
         const uint32_t q = kLaneBytes / 4 + (first_bit >> 5);
         pos = first_bit & 31u;
         lo = words[min(q, last_word)];
         hi = words[min(q + 1u, last_word)];
         next = q + 2u;
+        const uint32_t w = min(kLaneBytes / 4 + (end_bit >> 5), last_word);     // >= 16, so the indices below stay >= 14
+        dpos = end_bit & 31u;
+        dhi = words[w];
+        dlo = words[w - 1u];
+        dnext = w - 2u;
     }
 
-    // Decodes this lane's eight exponent bytes of one tile.  tab: the workgroup's table, 256 entries of
-    // length | symbol << 8; full_table / max_len: the tensor's decode table (symbol | length << 8) and its
-    // index width, read only for codes longer than 8 bits.
-    __device__ __forceinline__ uint2 tile(const uint16_t *tab, const uint16_t *full_table, uint32_t max_len)
+    // One lookup: the entry (length | symbol << 8) of the code that starts at bit (acc & 31) of win.
+    __device__ __forceinline__ uint32_t lookup(const uint16_t *tab, const uint16_t *full_table, uint32_t max_len,
+                                               uint32_t win, uint32_t acc)
     {
-        uint32_t e[2] = {0u, 0u};
-#pragma unroll
-        for (int r = 0; r < 8 / R; ++r) {
-            // the word this lane takes if the round crosses a word boundary: asked for now, used after the round
-            const uint32_t fresh = words[min(next, last_word)];
-            // R symbols out of one 32-bit window.  acc sums the entries: its low byte is the bit offset of the
-            // next code in the window (at most 32), the bytes above hold a sum of symbols that nothing reads.
-            // The field extract takes the low five bits of acc as its offset; when they wrap (32 bits used) no
-            // further code is extracted.
-            const uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
-            uint32_t acc = 0;
-            uint32_t s[R];
-#pragma unroll
-            for (int k = 0; k < R; ++k) {
-                uint32_t v = tab[__builtin_amdgcn_ubfe(win, acc, 8)];
-                if constexpr (R == 2) {
-                    if (__builtin_amdgcn_ballot_w64((v & 0xffu) > 8u)) {          // some lane of the wave has a long code
-                        if ((v & 0xffu) > 8u) {
-                            const uint32_t full = full_table[(win >> (acc & 31u)) & ((1u << max_len) - 1u)];
-                            v = __builtin_amdgcn_perm(0u, full, 0x0c0c0001u);      // symbol | length << 8  ->  length | symbol << 8
-                        }
-                    }
+        uint32_t v = tab[__builtin_amdgcn_ubfe(win, acc, 8)];
+        if constexpr (R == 2) {
+            if (__builtin_amdgcn_ballot_w64((v & 0xffu) > 8u)) {          // some lane of the wave has a long code
+                if ((v & 0xffu) > 8u) {
+                    const uint32_t full = full_table[(win >> (acc & 31u)) & ((1u << max_len) - 1u)];
+                    v = __builtin_amdgcn_perm(0u, full, 0x0c0c0001u);      // symbol | length << 8  ->  length | symbol << 8
                 }
-                s[k] = v;
-                acc += v;
             }
-            pos += acc & 0xffu;
-            // byte 1 (the symbol) of each entry, packed with byte permutes (0x0c selects a zero byte)
-            const uint32_t s01 = __builtin_amdgcn_perm(s[1], s[0], 0x0c0c0501u);
-            if constexpr (R == 4) e[r] = __builtin_amdgcn_perm(__builtin_amdgcn_perm(s[3], s[2], 0x0c0c0501u), s01, 0x05040100u);
-            else e[r >> 1] = (r & 1) ? __builtin_amdgcn_perm(s01, e[r >> 1], 0x05040100u) : s01;
-            // written without branches so that (with short codes) the whole tile is one basic block
-            const bool take = pos >= 32u;
-            lo = take ? hi : lo;
-            hi = take ? fresh : hi;
-            next += take ? 1u : 0u;
-            pos &= 31u;
         }
-        return make_uint2(e[0], e[1]);
+        return v;
+    }
+
+    // One round: R symbols of each chain.  up / down receive the R entries in the order read.
+    __device__ __forceinline__ void round(const uint16_t *tab, const uint16_t *full_table, uint32_t max_len,
+                                          uint32_t (&up)[R], uint32_t (&down)[R])
+    {
+        // the words the chains take if the round crosses a word boundary: asked for now, used after the round
+        const uint32_t fresh = words[min(next, last_word)];
+        const uint32_t dfresh = words[min(dnext, last_word)];
+        // R symbols out of one 32-bit window per chain.  acc sums the entries: its low byte is the bit offset of
+        // the next code in the window (at most 32), the bytes above hold a sum of symbols that nothing reads.
+        // The field extract takes the low five bits of acc as its offset; when they wrap (32 bits used) no
+        // further code is extracted.  The downward window is reversed so that its next bit is bit 0 too.
+        const uint32_t win = __builtin_amdgcn_alignbit(hi, lo, pos);
+        const uint32_t dwin = __builtin_bitreverse32(__builtin_amdgcn_alignbit(dhi, dlo, dpos));
+        uint32_t acc = 0, dacc = 0;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            up[k] = lookup(tab, full_table, max_len, win, acc);
+            down[k] = lookup(tab, full_table, max_len, dwin, dacc);
+            acc += up[k];
+            dacc += down[k];
+        }
+        // written without branches so that (with short codes) a whole tile pair is one basic block
+        pos += acc & 0xffu;
+        const bool take = pos >= 32u;
+        lo = take ? hi : lo;
+        hi = take ? fresh : hi;
+        next += take ? 1u : 0u;
+        pos &= 31u;
+        const int32_t left = static_cast<int32_t>(dpos) - static_cast<int32_t>(dacc & 0xffu);    // -32..31
+        const bool dtake = left < 0;
+        dhi = dtake ? dlo : dhi;
+        dlo = dtake ? dfresh : dlo;
+        dnext -= dtake ? 1u : 0u;
+        dpos = static_cast<uint32_t>(left) & 31u;
+    }
+
+    // Four symbols of each chain: .x = the upward chain's, .y = the downward chain's, both packed in value order
+    // (byte 0 = the symbol with the lowest index), i.e. half a tile's exponent bytes for this lane each.
+    __device__ __forceinline__ uint2 quad(const uint16_t *tab, const uint16_t *full_table, uint32_t max_len)
+    {
+        // byte 1 (the symbol) of each entry, packed with byte permutes (0x0c selects a zero byte)
+        if constexpr (R == 4) {
+            uint32_t up[4], down[4];
+            round(tab, full_table, max_len, up, down);
+            const uint32_t u01 = __builtin_amdgcn_perm(up[1], up[0], 0x0c0c0501u), u23 = __builtin_amdgcn_perm(up[3], up[2], 0x0c0c0501u);
+            const uint32_t d01 = __builtin_amdgcn_perm(down[2], down[3], 0x0c0c0501u), d23 = __builtin_amdgcn_perm(down[0], down[1], 0x0c0c0501u);
+            return make_uint2(__builtin_amdgcn_perm(u23, u01, 0x05040100u), __builtin_amdgcn_perm(d23, d01, 0x05040100u));
+        } else {
+            uint32_t ua[2], da[2], ub[2], db[2];
+            round(tab, full_table, max_len, ua, da);
+            round(tab, full_table, max_len, ub, db);
+            const uint32_t u01 = __builtin_amdgcn_perm(ua[1], ua[0], 0x0c0c0501u), u23 = __builtin_amdgcn_perm(ub[1], ub[0], 0x0c0c0501u);
+            const uint32_t d01 = __builtin_amdgcn_perm(db[0], db[1], 0x0c0c0501u), d23 = __builtin_amdgcn_perm(da[0], da[1], 0x0c0c0501u);
+            return make_uint2(__builtin_amdgcn_perm(u23, u01, 0x05040100u), __builtin_amdgcn_perm(d23, d01, 0x05040100u));
+        }
     }
 };
 
@@ -264,24 +304,21 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         }
     }
     // Next in the request order: the sign-mantissa bytes of the first tiles.  They stay in flight while the
-    // stream is staged and decoding starts.  With ordinary stores a straight-line stream asks for its first
-    // kAhead tiles here and for tile k + kAhead when tile k is done: the requests of the thousands of waves that
-    // start together are spread out, everyone's first tile arrives sooner (one layer call of 118 MB: 64.5 -> 70 %
-    // of the roofline with cache-resident outputs, 56 -> 58.5 % with cold ones).  A wave waits for such a later
-    // load behind its own earlier stores, though, and non-temporal stores take long to be acknowledged: with
-    // them all eight tiles are asked for up front (rolling requests there: between -4 % and +3 %).
-    constexpr int kAhead = kStreaming ? kGroup : 4;
+    // stream is staged and decoding starts.  A straight-line stream is decoded from both ends: pair i is tile i
+    // (upward chain) and tile 7 - i of the group (downward chain); up[i] / down[i] hold their bytes.
+    // With ordinary stores the first kAhead pairs are asked for here and pair i + kAhead when pair i is done:
+    // the requests of the thousands of waves that start together are spread out and everyone's first tiles
+    // arrive sooner.  A wave waits for such a later load behind its own earlier stores, though, and non-temporal
+    // stores take long to be acknowledged: with them all eight tiles are asked for up front.
+    constexpr int kPairs = kGroup / 2;
+    constexpr int kAhead = kStreaming ? kPairs : 2;
     const bool straight = full && mode == ZM_MODE_CODED;
-    uint2 sm[kGroup];
+    uint2 up[kPairs], down[kPairs];
     if (straight) {
 #pragma unroll
-        for (int k = 0; k < kAhead; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
-    } else {
-#pragma unroll
-        for (int k = 0; k < kGroup; ++k) {
-            sm[k] = make_uint2(0u, 0u);
-            if (static_cast<uint32_t>(k) < tiles && mine - static_cast<int32_t>(k * kTile) > 0)
-                sm[k] = *reinterpret_cast<const uint2 *>(sm_base + k * kTile);
+        for (int i = 0; i < kAhead; ++i) {
+            up[i] = *reinterpret_cast<const uint2 *>(sm_base + i * kTile);
+            down[i] = *reinterpret_cast<const uint2 *>(sm_base + (tiles - 1u - i) * kTile);
         }
     }
 
@@ -318,47 +355,66 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
         // a6: this lane's bitstream has 8 * tiles + quantum * (its length byte) bits and starts where
         // the bitstreams of the lanes below it end
         const uint32_t units = reinterpret_cast<const uint8_t *>(words)[lane];
-        dec.start(wave_exclusive_sum(8u * tiles + quantum * units));
+        const uint32_t bits = 8u * tiles + quantum * units;
+        const uint32_t first = wave_exclusive_sum(bits);
+        dec.start(first, first + bits);
     }
 
     if (straight) {
         // Common case, straight-line: a coded stream of whole groups of kGroup tiles (one group at the
-        // default stream length).  The first group's loads were issued above (the rest of them follow tile by
-        // tile); from here on the wave only computes and stores, and asks for the next group's sign-mantissa
+        // default stream length).  Group number q is the tiles 4q..4q+3 (upward chain) and, from the other
+        // end, tiles - 1 - 4q down to tiles - 4 - 4q (downward chain).  The first group's loads were issued
+        // above; from here on the wave only computes and stores, and asks for the next group's sign-mantissa
         // bytes when a group is done.
-        const uint32_t groups = sn / (kGroup * kTile);
+        const uint32_t groups = tiles / kGroup;
         for (uint32_t q = 0;;) {
+            const uint32_t lo_tile = q * kPairs, hi_tile = tiles - 1u - q * kPairs;
 #pragma unroll
-            for (int k = 0; k < kGroup; ++k) {
-                recover_and_store<kStreaming>(out_base + (q * kGroup + k) * kTile, dec.tile(tab, full_table, max_len), sm[k]);
-                if (q == 0 && k + kAhead < kGroup) sm[k + kAhead] = *reinterpret_cast<const uint2 *>(sm_base + (k + kAhead) * kTile);
+            for (int i = 0; i < kPairs; ++i) {
+                // a tile's eight symbols come in two quads: the upward chain gives values 0..3 first, the
+                // downward chain values 4..7 first
+                const uint2 a = dec.quad(tab, full_table, max_len), b = dec.quad(tab, full_table, max_len);
+                recover_and_store<kStreaming>(out_base + (lo_tile + i) * kTile, make_uint2(a.x, b.x), up[i]);
+                recover_and_store<kStreaming>(out_base + (hi_tile - i) * kTile, make_uint2(b.y, a.y), down[i]);
+                if (q == 0 && i + kAhead < kPairs) {
+                    up[i + kAhead] = *reinterpret_cast<const uint2 *>(sm_base + (i + kAhead) * kTile);
+                    down[i + kAhead] = *reinterpret_cast<const uint2 *>(sm_base + (tiles - 1u - (i + kAhead)) * kTile);
+                }
             }
             if (++q == groups) break;
 #pragma unroll
-            for (int k = 0; k < kGroup; ++k) sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (q * kGroup + k) * kTile);
+            for (int i = 0; i < kPairs; ++i) {
+                up[i] = *reinterpret_cast<const uint2 *>(sm_base + (q * kPairs + i) * kTile);
+                down[i] = *reinterpret_cast<const uint2 *>(sm_base + (tiles - 1u - q * kPairs - i) * kTile);
+            }
         }
     } else {
         // General case: raw chunks, short last streams, streams that are not whole groups of kGroup tiles.
-        for (uint32_t g0 = 0; g0 < tiles; g0 += kGroup) {
-            if (g0) {
-#pragma unroll
-                for (int k = 0; k < kGroup; ++k) {
-                    sm[k] = make_uint2(0u, 0u);
-                    if (g0 + k < tiles && mine - static_cast<int32_t>((g0 + k) * kTile) > 0)
-                        sm[k] = *reinterpret_cast<const uint2 *>(sm_base + (g0 + k) * kTile);
-                }
+        // Pair p is tile p and tile tiles - 1 - p; with an odd number of tiles the last pair is the middle
+        // tile alone, whose low half comes from the upward and whose high half from the downward chain.
+        auto load_sm = [&](uint32_t tile) {
+            return mine - static_cast<int32_t>(tile * kTile) > 0 ? *reinterpret_cast<const uint2 *>(sm_base + tile * kTile)
+                                                                   : make_uint2(0u, 0u);
+        };
+        auto finish = [&](uint32_t tile, uint2 ev, uint2 smv) {
+            const int32_t left = mine - static_cast<int32_t>(tile * kTile);
+            if (mode != ZM_MODE_CODED) ev = left > 0 ? *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u) : make_uint2(0u, 0u);
+            if (left >= 8) recover_and_store<kStreaming>(out_base + tile * kTile, ev, smv);
+            else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, smv, left);
+        };
+        for (uint32_t p = 0; 2u * p < tiles; ++p) {
+            const uint32_t lo_tile = p, hi_tile = tiles - 1u - p;
+            const uint2 sm_lo = load_sm(lo_tile), sm_hi = load_sm(hi_tile);
+            uint2 a = make_uint2(0u, 0u), b = a;
+            if (mode == ZM_MODE_CODED) {
+                a = dec.quad(tab, full_table, max_len);
+                if (lo_tile != hi_tile) b = dec.quad(tab, full_table, max_len);
             }
-#pragma unroll
-            for (int k = 0; k < kGroup; ++k) {
-                const uint32_t tile = g0 + k;
-                if (tile < tiles) {
-                    const int32_t left = mine - static_cast<int32_t>(tile * kTile);
-                    uint2 ev = make_uint2(0u, 0u);
-                    if (mode == ZM_MODE_CODED) ev = dec.tile(tab, full_table, max_len);
-                    else if (left > 0) ev = *reinterpret_cast<const uint2 *>(raw + tile * kTile + lane * 8u);
-                    if (left >= 8) recover_and_store<kStreaming>(out_base + tile * kTile, ev, sm[k]);
-                    else if (left > 0) recover_and_store_partial(out_base + tile * kTile, ev, sm[k], left);
-                }
+            if (lo_tile != hi_tile) {
+                finish(lo_tile, make_uint2(a.x, b.x), sm_lo);
+                finish(hi_tile, make_uint2(b.y, a.y), sm_hi);
+            } else {
+                finish(lo_tile, make_uint2(a.x, a.y), sm_lo);
             }
         }
     }

@@ -20,7 +20,7 @@
 namespace {
 
 constexpr uint32_t kMagic = 0x454F4D5Au;   // "ZMOE"
-constexpr uint32_t kVersion = 3;
+constexpr uint32_t kVersion = 4;
 constexpr uint32_t kHeaderBytes = 128;
 constexpr uint32_t kLanes = 64;
 constexpr uint32_t kRun = 8;               // consecutive values per lane per tile
@@ -61,6 +61,7 @@ inline uint32_t lane_quantum_for(uint32_t max_len, uint32_t stream_values)
 struct Book {
     uint8_t len[256];
     uint16_t wire[256];   // code with its first wire bit in bit 0 (ready for LSB-first packing)
+    uint16_t canon[256];  // the same code with its first wire bit in its top bit (the canonical code value)
     uint32_t max_len = 1;
     uint32_t n_present = 0;
     uint32_t pad = 0;
@@ -75,7 +76,7 @@ bool make_book(const uint8_t code_len[256], Book &b)
         const uint32_t l = code_len[s];
         if (l > ZM_MAX_CODE_LEN) return false;
         b.len[s] = static_cast<uint8_t>(l);
-        b.wire[s] = 0;
+        b.wire[s] = 0; b.canon[s] = 0;
         if (l) { ++count[l]; ++b.n_present; b.kraft += 1u << (ZM_MAX_CODE_LEN - l); b.max_len = std::max(b.max_len, l); }
     }
     if (b.kraft > (1u << ZM_MAX_CODE_LEN)) return false;
@@ -91,6 +92,7 @@ bool make_book(const uint8_t code_len[256], Book &b)
             uint32_t rev = 0;
             for (uint32_t k = 0; k < l; ++k) rev |= ((c >> k) & 1u) << (l - 1 - k);
             b.wire[s] = static_cast<uint16_t>(rev);
+            b.canon[s] = static_cast<uint16_t>(c);
             if (!pad_set) { b.pad = static_cast<uint32_t>(s); pad_set = true; }
             ++c;
         }
@@ -118,7 +120,9 @@ size_t stream_byte_bound(uint32_t stream_values)
 }
 
 // Packs exponents e[0..n) of one stream: 64 length bytes, then the lanes' bitstreams back to back (LSB first),
-// zero bits to a multiple of 16 bytes.  Returns the bytes written.
+// zero bits to a multiple of 16 bytes.  A lane's bitstream holds the codes of its first half of symbols from its
+// first bit upwards and those of its second half, last symbol first, from its last bit downwards; the unused
+// bits sit in the middle.  Returns the bytes written.
 size_t pack_stream(const uint8_t *e, uint32_t n, const Book &b, uint32_t quantum, uint8_t *out)
 {
     const uint32_t tiles = (n + kTile - 1) / kTile;
@@ -132,24 +136,25 @@ size_t pack_stream(const uint8_t *e, uint32_t n, const Book &b, uint32_t quantum
         fill += count;
         while (fill >= 8) { payload[at++] = static_cast<uint8_t>(acc); acc >>= 8; fill -= 8; }
     };
+    auto symbol = [&](uint32_t lane, uint32_t j) -> uint32_t {
+        const uint32_t idx = (j / kRun) * kTile + lane * kRun + (j % kRun);
+        return idx < n ? e[idx] : b.pad;
+    };
     for (uint32_t lane = 0; lane < kLanes; ++lane) {
         uint32_t used = 0;
-        for (uint32_t t = 0; t < tiles; ++t) {
-            const uint32_t base = t * kTile + lane * kRun;
-            for (uint32_t i = 0; i < kRun; ++i) {
-                const uint32_t idx = base + i;
-                const uint32_t s = idx < n ? e[idx] : b.pad;
-                put(b.wire[s], b.len[s]);
-                used += b.len[s];
-            }
-        }
+        for (uint32_t j = 0; j < syms; ++j) used += b.len[symbol(lane, j)];
         const uint32_t units = (used - syms + quantum - 1) / quantum;
         out[lane] = static_cast<uint8_t>(units);
+        // in ascending bit order: the first half's codes, first bit lowest; the zero bits in the middle; the
+        // second half's codes from the half's first symbol (read last) to the lane's last symbol (read first),
+        // each with its first bit highest
+        for (uint32_t j = 0; j < syms / 2; ++j) { const uint32_t s = symbol(lane, j); put(b.wire[s], b.len[s]); }
         for (uint32_t fillers = syms + quantum * units - used; fillers; ) {
             const uint32_t k = std::min(fillers, 32u);
             put(0, k);
             fillers -= k;
         }
+        for (uint32_t j = syms / 2; j < syms; ++j) { const uint32_t s = symbol(lane, j); put(b.canon[s], b.len[s]); }
     }
     if (fill) put(0, 8 - fill);
     const size_t total = align_up(kLanes + at, 16);
@@ -232,8 +237,9 @@ void package_merge(const std::vector<uint64_t> &weight, int max_len, std::vector
 
 
 // Table-driven decode of one stream on the host: the prefix sum over the length bytes gives every lane's
-// first bit; each lane is then decoded on its own through a 64-bit window.
-// lut: 2^max_len entries (symbol | length << 8).  Returns false if a lane would read past the stream.
+// first and last bit; each lane is decoded on its own, its first half of symbols upwards through one 64-bit
+// buffer and its second half downwards through another, a symbol of each per step.
+// lut: 2^max_len entries (symbol | length << 8).  Returns false if a lane's halves would run into each other.
 bool unpack_stream(const uint8_t *stream, size_t n_bytes, uint32_t n, const uint8_t *lut, uint32_t max_len,
                    uint32_t quantum, uint8_t *e)
 {
@@ -244,24 +250,39 @@ bool unpack_stream(const uint8_t *stream, size_t n_bytes, uint32_t n, const uint
     const uint8_t *payload = stream + kLanes;
     const size_t payload_words = (n_bytes - kLanes) / 4;
     const uint64_t payload_bits = payload_words * 32ull;
-    auto word = [&](size_t i) -> uint64_t { return i < payload_words ? load_le<uint32_t>(payload + 4 * i) : 0u; };   // zeros past the end
+    auto word = [&](size_t i) -> uint64_t { return i < payload_words ? load_le<uint32_t>(payload + 4 * i) : 0u; };   // zeros outside
+    auto place = [&](uint32_t lane, uint32_t j, uint32_t sym) {
+        const uint32_t idx = (j / kRun) * kTile + lane * kRun + (j % kRun);
+        if (idx < n) e[idx] = static_cast<uint8_t>(sym);
+    };
     uint64_t start = 0;
     for (uint32_t lane = 0; lane < kLanes; ++lane) {
         const uint64_t span = syms + static_cast<uint64_t>(quantum) * stream[lane];
         if (start + span > payload_bits) return false;
-        // a 64-bit buffer over the lane's bitstream, topped up a word at a time: at least 32 valid bits before a lookup
-        size_t next = start >> 5;
-        uint64_t buffer = (word(next) | word(next + 1) << 32) >> (start & 31);
-        uint32_t valid = 64 - static_cast<uint32_t>(start & 31);
-        next += 2;
+        // upwards: the next bit is bit 0 of `up`; at least 32 valid bits before a lookup
+        size_t next_up = start >> 5;
+        uint64_t up = (word(next_up) | word(next_up + 1) << 32) >> (start & 31);
+        uint32_t up_valid = 64 - static_cast<uint32_t>(start & 31);
+        next_up += 2;
+        // downwards: the next bit is bit 63 of `down`
+        const uint64_t end = start + span;
+        size_t next_down = end >> 5;                       // the word that holds the bits just below `end`, if end is not word-aligned
+        uint32_t down_valid = static_cast<uint32_t>(end & 31);
+        uint64_t down = down_valid ? word(next_down) << (64 - down_valid) : 0;
+        --next_down;                                       // wraps past zero to an index outside the payload: reads as zero
+        while (down_valid <= 32) { down |= word(next_down--) << (32 - down_valid); down_valid += 32; }
         uint64_t used = 0;
-        for (uint32_t j = 0; j < syms; ++j) {
-            const uint32_t x = static_cast<uint32_t>(buffer) & mask;
-            const uint32_t idx = (j / kRun) * kTile + lane * kRun + (j % kRun);
-            if (idx < n) e[idx] = lut[2 * x];
-            const uint32_t len = lut[2 * x + 1];
-            buffer >>= len; valid -= len; used += len;
-            if (valid <= 32) { buffer |= word(next++) << valid; valid += 32; }
+        for (uint32_t step = 0; step < syms / 2; ++step) {
+            const uint32_t a = static_cast<uint32_t>(up) & mask;
+            const uint32_t z = __builtin_bitreverse32(static_cast<uint32_t>(down >> 32)) & mask;
+            place(lane, step, lut[2 * a]);
+            place(lane, syms - 1 - step, lut[2 * z]);
+            const uint32_t la = lut[2 * a + 1], lz = lut[2 * z + 1];
+            up >>= la; up_valid -= la;
+            down <<= lz; down_valid -= lz;
+            used += la + lz;
+            if (up_valid <= 32) { up |= word(next_up++) << up_valid; up_valid += 32; }
+            if (down_valid <= 32) { down |= word(next_down--) << (32 - down_valid); down_valid += 32; }
         }
         if (used > span) return false;
         start += span;
