@@ -309,9 +309,10 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     // With ordinary stores the first kAhead pairs are asked for here and pair i + kAhead when pair i is done:
     // the requests of the thousands of waves that start together are spread out and everyone's first tiles
     // arrive sooner.  A wave waits for such a later load behind its own earlier stores, though, and non-temporal
-    // stores take long to be acknowledged: with them all eight tiles are asked for up front.
+    // stores take long to be acknowledged: with them all eight tiles are asked for up front.  So they are with
+    // long codes, whose look-ups in device memory would wait behind the later requests as well.
     constexpr int kPairs = kGroup / 2;
-    constexpr int kAhead = kStreaming ? kPairs : 2;
+    constexpr int kAhead = (kStreaming || R == 2) ? kPairs : 2;
     const bool straight = full && mode == ZM_MODE_CODED;
     uint2 up[kPairs], down[kPairs];
     if (straight) {

@@ -20,8 +20,9 @@ def say(msg):
     sys.stdout.flush()
 
 
-def gpu_decode_tensors(blobs, repeat_ids=None):
-    """Decodes each blob as a one-tensor expert; returns the decoded uint16 arrays (with guard check)."""
+def gpu_decode_tensors(blobs, repeat_ids=None, stores=None):
+    """Decodes each blob as a one-tensor expert; returns the decoded uint16 arrays (with guard check).
+    stores: None = zm_decode_experts, else the policy handed to zm_decode_experts_stores."""
     import torch
     layer = zm.ExpertLayer([[b] for b in blobs])
     ids = list(range(len(blobs))) if repeat_ids is None else repeat_ids
@@ -33,9 +34,15 @@ def gpu_decode_tensors(blobs, repeat_ids=None):
         outs.append(buf)
         ptrs[j] = buf.data_ptr() + 2 * GUARD
     idarr = (ctypes.c_int32 * len(ids))(*ids)
-    zm.decode_experts(layer._ptr_blobs, layer._ptr_tables, layer._ptr_infos, layer.n_experts, 1,
-                      idarr, len(ids), ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p)),
-                      torch.cuda.current_stream().cuda_stream)
+    outp = ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p))
+    stream = torch.cuda.current_stream().cuda_stream
+    if stores is None:
+        zm.decode_experts(layer._ptr_blobs, layer._ptr_tables, layer._ptr_infos, layer.n_experts, 1, idarr, len(ids), outp, stream)
+    else:
+        rc = zm.lib().zm_decode_experts_stores(layer._ptr_blobs, layer._ptr_tables, layer._ptr_infos, layer.n_experts, 1,
+                                               idarr, len(ids), outp, stores, ctypes.c_void_p(stream))
+        if rc != zm.OK:
+            raise zm.ZipMoEError(rc, "zm_decode_experts_stores")
     torch.cuda.synchronize()
     res = []
     for buf in outs:
@@ -62,10 +69,12 @@ def test_edge_cases_bit_exact(C, W, max_len):
             tensors.append(w)
             blobs.append(blob)
     say(f"edge cases C={C} W={W} L<={max_len}: {len(blobs)} tensors in one call")
-    got = gpu_decode_tensors(blobs)
-    for w, blob, g in zip(tensors, blobs, got):
-        assert np.array_equal(g, zo.decode(blob))        # against the reference decoder
-        assert np.array_equal(g, w)                      # and against the original: lossless
+    refs = [zo.decode(blob) for blob in blobs]
+    for stores in (None, zm.STORES_CACHED, zm.STORES_STREAMING):      # the library's own choice, and both kernels by name
+        got = gpu_decode_tensors(blobs, stores=stores)
+        for w, ref, g in zip(tensors, refs, got):
+            assert np.array_equal(g, ref)                    # against the reference decoder
+            assert np.array_equal(g, w)                      # and against the original: lossless
 
 
 def test_all_bit_patterns_and_duplicates():
