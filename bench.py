@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published peak HBM3E bandwidth
 # copy of known size; the summaries are under profiles/).  Valid only for the kernel source they were taken
 # with: the entry is reported only while the source's hash still matches, else "traffic" is null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256_16": "17c2549843cc6aa7",
-    "bytes_per_launch": {"cfg5": 117.13e6, "cfg3": 170.37e6, "cfg4": 1195.77e6, "split-cfg4": 234.91e6},
+    "kernel_sha256_16": "2c7e12c4afcaa219",
+    "bytes_per_launch": {"cfg5": 117.14e6, "cfg3": 170.40e6, "cfg4": 1195.80e6, "split-cfg4": 234.91e6},
 }
 
 
