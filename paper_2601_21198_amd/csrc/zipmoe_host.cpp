@@ -239,13 +239,15 @@ void package_merge(const std::vector<uint64_t> &weight, int max_len, std::vector
 // Table-driven decode of one stream on the host: the prefix sum over the length bytes gives every lane's
 // first and last bit; each lane is decoded on its own, its first half of symbols upwards through one 64-bit
 // buffer and its second half downwards through another, a symbol of each per step.
-// lut: 2^max_len entries (symbol | length << 8).  Returns false if a lane's halves would run into each other.
+// lut: 2^max_len entries (symbol, length) indexed by the next max_len bits with the first bit lowest, followed by
+// 2^max_len entries indexed with the first bit highest.  Returns false if a lane's halves would run into each other.
 bool unpack_stream(const uint8_t *stream, size_t n_bytes, uint32_t n, const uint8_t *lut, uint32_t max_len,
                    uint32_t quantum, uint8_t *e)
 {
     const uint32_t tiles = (n + kTile - 1) / kTile;
     const uint32_t syms = tiles * kRun;
     const uint32_t mask = (1u << max_len) - 1u;
+    const uint8_t *mirror = lut + (2u << max_len);
     if (n_bytes < kLanes) return false;
     const uint8_t *payload = stream + kLanes;
     const size_t payload_words = (n_bytes - kLanes) / 4;
@@ -274,10 +276,10 @@ bool unpack_stream(const uint8_t *stream, size_t n_bytes, uint32_t n, const uint
         uint64_t used = 0;
         for (uint32_t step = 0; step < syms / 2; ++step) {
             const uint32_t a = static_cast<uint32_t>(up) & mask;
-            const uint32_t z = __builtin_bitreverse32(static_cast<uint32_t>(down >> 32)) & mask;
+            const uint32_t z = static_cast<uint32_t>(down >> (64 - max_len));
             place(lane, step, lut[2 * a]);
-            place(lane, syms - 1 - step, lut[2 * z]);
-            const uint32_t la = lut[2 * a + 1], lz = lut[2 * z + 1];
+            place(lane, syms - 1 - step, mirror[2 * z]);
+            const uint32_t la = lut[2 * a + 1], lz = mirror[2 * z + 1];
             up >>= la; up_valid -= la;
             down <<= lz; down_valid -= lz;
             used += la + lz;
@@ -551,8 +553,15 @@ int zm_decode_exponents_host(const void *blob_host, size_t size, uint32_t chunk_
     std::atomic<int> status{ZM_OK};
     std::vector<std::thread> pool;
     try {
-        std::vector<uint8_t> lut(2u << t.max_len);
+        // two tables: the blob's (indexed by the next max_len bits, first bit lowest) for the upward chain and its
+        // mirror (first bit highest) for the downward chain
+        std::vector<uint8_t> lut(4u << t.max_len);
         fill_decode_table(book, lut.data());
+        for (uint32_t x = 0; x < (1u << t.max_len); ++x) {
+            const uint32_t y = __builtin_bitreverse32(x) >> (32 - t.max_len);
+            lut[(2u << t.max_len) + 2 * x] = lut[2 * y];
+            lut[(2u << t.max_len) + 2 * x + 1] = lut[2 * y + 1];
+        }
         auto work = [&]() {
             for (;;) {
                 const uint32_t c = next_chunk.fetch_add(1);
