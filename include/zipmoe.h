@@ -48,15 +48,21 @@
  *              streams one after the other.
  *              A stream covers stream_values consecutive values, cut into
  *              tiles of 512; in every tile lane j of 64 owns values 8j..8j+7.
- *              A lane's bitstream is the codes of its m symbols (8 per tile,
- *              tile after tile; positions past the stream's end hold the
- *              first symbol in canonical order), first code bit first,
- *              followed by zero bits up to D = m + q*b bits, b the smallest
- *              byte that fits.  The stream is the 64 bytes b (lane 0 first),
+ *              A lane has m symbols (8 per tile, tile after tile; positions
+ *              past the stream's end hold the first symbol in canonical order)
+ *              and a bitstream of D = m + q*b bits, b the smallest byte that
+ *              fits their codes.  The bitstream is filled from both ends: the
+ *              codes of symbols 0..m/2-1 upwards from its first bit, first
+ *              code bit first; the codes of symbols m-1 down to m/2 downwards
+ *              from its last bit (symbol m-1's first code bit is the lane's
+ *              last bit, the next code bit the one below it); the bits in
+ *              between are zero.  A decoder can so run two independent chains
+ *              per lane.  The stream is the 64 bytes b (lane 0 first),
  *              then the 64 bitstreams back to back with no gap (payload bit k
  *              is bit k%32 of the little-endian 32-bit word k/32), then zero
  *              bits to a multiple of 16 bytes.  A prefix sum over the 64 bytes
- *              gives every lane's first bit.  q, the header's lane_quantum, is
+ *              gives every lane's first bit and, with it, the lane before's
+ *              last.  q, the header's lane_quantum, is
  *              the smallest integer >= 1 with (L-1)*(stream_values/64) <= 255*q.
  */
 #ifndef ZIPMOE_H
