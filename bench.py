@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published peak HBM3E bandwidth
 # copy of known size; the summaries are under profiles/).  Valid only for the kernel source they were taken
 # with: the entry is reported only while the source's hash still matches, else "traffic" is null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256_16": "2c7e12c4afcaa219",
-    "bytes_per_launch": {"cfg5": 117.14e6, "cfg3": 170.40e6, "cfg4": 1195.80e6, "split-cfg4": 234.91e6},
+    "kernel_sha256_16": "ce9dabce4bdecb09",
+    "bytes_per_launch": {"cfg5": 117.14e6, "cfg3": 170.40e6, "cfg4": 1195.80e6, "split-cfg4": 234.96e6},
 }
 
 
@@ -161,7 +161,8 @@ def bench_split(args, wl, workers: int, steps: int, warmup: int) -> int:
         "config": {"workload": wl.name, "path": "split", "tensors_per_step": len(dev), "values_per_step": n_total},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic("split-" + args.workload),
-                     "kernel": "zm_recover_kernel",
+                     # the library stores non-temporally when a launch moves more than 128 MiB (4 bytes per value)
+                     "kernel": "zm_recover_kernel<%s>" % ("true" if 4 * max(h[2] for h in dev) > (128 << 20) else "false"),
                      "us_per_launch": round(kernel_s * 1e6, 2), "algorithmic_bytes_per_launch": alg},
         "host_decode": {"value": round(2.0 * n_total / host_dt / 1e9, 3), "unit": "GB/s of bf16", "threads": workers,
                         "note": "zm_decode_exponents_host over the same tensors, one after the other"},

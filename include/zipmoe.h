@@ -451,7 +451,8 @@ int zm_decode_exponents_host(const void *blob_host, size_t size, uint32_t chunk_
  * n_values sign-mantissa bytes (both DEVICE, 8-byte aligned) into n_values bf16
  * words (DEVICE, 16-byte aligned) with vector loads and stores:
  * word = sign << 15 | exponent << 7 | mantissa.  Asynchronous on `stream`
- * (a hipStream_t), allocates nothing.  ZM_E_ARG for null or misaligned
+ * (a hipStream_t), allocates nothing.  Tensors of more than 32 Mi values are
+ * written with non-temporal stores (they do not stay in the last-level cache).  ZM_E_ARG for null or misaligned
  * pointers, ZM_E_HIP if the launch fails. */
 int zm_recover(const void *exponents, const void *sign_mantissa, size_t n_values, void *out_bf16, void *stream);
 

@@ -32,6 +32,15 @@ def test_recover_matches_reference_merge(n):
     assert np.array_equal(gpu_recover(e, sm), zo.merge(e, sm))
 
 
+def test_recover_launch_larger_than_half_the_last_level_cache():
+    """a launch that moves more than 128 MB stores non-temporally: same words; the length is no multiple of a tile"""
+    n = (40 << 20) + 1237
+    rng = np.random.default_rng(77)
+    e = rng.integers(0, 256, n, dtype=np.uint8)
+    sm = rng.integers(0, 256, n, dtype=np.uint8)
+    assert np.array_equal(gpu_recover(e, sm), zo.merge(e, sm))
+
+
 def test_recover_all_pairs():
     e = np.repeat(np.arange(256, dtype=np.uint8), 256)
     sm = np.tile(np.arange(256, dtype=np.uint8), 256)
