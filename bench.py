@@ -98,6 +98,17 @@ def cpu_baseline(sample_blobs, workers: int, min_seconds: float = 10.0):
     return 2.0 * total / dt / 1e9, total, dt, passes
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def reference_copy(mib: int) -> None:
     """A plain device-to-device copy of known size, so that a profiler's byte counters read in the same run
     can be scaled to bytes."""
@@ -547,6 +558,7 @@ def main() -> int:
                       f"{n} values decoded in {dt:.1f} s",
             "single_thread": {"value": round(one_gbps, 4), "unit": "GB/s", "cores": 1,
                               "sample": f"the first of these tensors, {one_n} values decoded in {one_dt:.1f} s"},
+            "host": {"cpu_model": cpu_model(), "os_cpu_count": os.cpu_count()},
         }
     print(json.dumps(result), flush=True)
     return 0

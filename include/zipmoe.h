@@ -191,7 +191,9 @@ int zm_validate_blob(const void *blob_host, size_t size);
  * Asynchronous: enqueues the launches on `stream` and returns; allocates
  * nothing, copies nothing, does not synchronise.  All arguments travel as
  * kernel arguments, so host arrays may be reused as soon as the call returns;
- * device buffers must stay valid until the stream has passed the call.
+ * device buffers must stay valid until the stream has passed the call.  For
+ * the same reason the call may be recorded on a capturing stream and replayed
+ * from the HIP graph: it records kernel launches and nothing else.
  * Blobs must have passed zm_validate_blob: the kernel confines every access to
  * the sizes in `infos`, it does not re-validate the streams.
  * At most 256 tensors (n_selected * tensors_per_expert) per call.
