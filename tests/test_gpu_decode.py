@@ -112,6 +112,68 @@ def test_mixed_geometries_in_one_call():
         assert np.array_equal(g, w) and np.array_equal(g, zo.decode(blob))
 
 
+def chunk_modes(blob):
+    """mode of every chunk (0 coded, 1 raw), read from the blob's chunk table"""
+    h = zo.header(blob)
+    table = np.asarray(blob[h["table_offset"]: h["table_offset"] + h["table_stride"] * h["n_chunks"]], np.uint8)
+    return table.reshape(h["n_chunks"], h["table_stride"])[:, 0] & 15
+
+
+def patchwork_tensor(rng, n):
+    """segments of very different exponent statistics in one tensor: with one codebook for the whole tensor some
+    chunks compress and others are stored raw, and streams differ widely in length"""
+    parts, left = [], n
+    while left > 0:
+        m = int(min(left, rng.integers(1, 40000)))
+        k = int(rng.integers(5))
+        if k == 0:
+            seg = rng.integers(0, 65536, m, dtype=np.uint16)                                     # incompressible
+        elif k == 1:
+            seg = np.full(m, 0x3F80, np.uint16) | rng.integers(0, 128, m, dtype=np.uint16)      # one exponent
+        elif k == 2:
+            seg = synth.bf16_round(rng.standard_normal(m, dtype=np.float32) * np.float32(10.0 ** rng.uniform(-4, 2)))
+        elif k == 3:
+            e = rng.geometric(0.5, m).clip(1, 40).astype(np.uint16) + 90                         # geometric exponents
+            seg = (e << 7) | rng.integers(0, 128, m, dtype=np.uint16) | (rng.integers(0, 2, m, dtype=np.uint16) << 15)
+        else:
+            e = rng.choice(np.array([1, 2, 127, 128, 254, 255], np.uint16), m, p=[0.5, 0.25, 0.12, 0.07, 0.04, 0.02])
+            seg = (e << 7) | rng.integers(0, 128, m, dtype=np.uint16)
+        parts.append(seg.astype(np.uint16))
+        left -= m
+    return np.concatenate(parts) if parts else np.zeros(0, np.uint16)
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_patchwork_tensors(seed):
+    rng = np.random.default_rng(seed)
+    geometries = [(4096, 512, 8), (4096, 4096, 8), (16384, 4096, 8), (16384, 4096, 12), (16384, 2048, 9), (8192, 8192, 8),
+                  (2048, 1024, 12), (16384, 16384, 10), (1024, 512, 8), (32768, 4096, 8)]
+    tensors, blobs, n_raw, n_coded = [], [], 0, 0
+    for i in range(64):
+        C, W, max_len = geometries[int(rng.integers(len(geometries)))]
+        w = patchwork_tensor(rng, int(rng.integers(1, 150000)))
+        n_present = np.unique(zo.split(w)[0]).size
+        while (1 << max_len) < n_present:
+            max_len += 1
+        if i % 2:
+            blob = zo.encode(w, C, W, zo.code_lengths(zo.histogram(zo.split(w)[0]), max_len))
+        else:
+            blob, _ = zm.compress(w, C, W, max_len)
+        modes = chunk_modes(blob)
+        n_raw += int((modes == 1).sum())
+        n_coded += int((modes == 0).sum())
+        tensors.append(w)
+        blobs.append(blob)
+    say(f"patchwork seed {seed}: {len(blobs)} tensors, {n_coded} coded and {n_raw} raw chunks")
+    assert n_raw > 20 and n_coded > 20
+    for stores in (None, zm.STORES_STREAMING):
+        got = gpu_decode_tensors(blobs, stores=stores)
+        for w, blob, g in zip(tensors, blobs, got):
+            assert np.array_equal(g, w)
+    for blob, w in list(zip(blobs, tensors))[::4]:
+        assert np.array_equal(zo.decode(blob), w)
+
+
 @pytest.mark.parametrize("kind,W,max_len", [("gauss", 4096, 8), ("wide", 4096, 12), ("wide", 16384, 12),
                                             ("wide", 32768, 12), ("gauss", 32768, 8)])
 def test_outputs_larger_than_the_last_level_cache(kind, W, max_len):
