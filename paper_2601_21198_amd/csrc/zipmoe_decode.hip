@@ -17,9 +17,11 @@
 //   1. one read of the chunk's table entry locates the stream; its bytes (64 lane-length bytes, then the 64
 //      lane bitstreams back to back) are requested with 128-bit loads (a4) -- first, because decoding can not
 //      start without them -- and go to LDS;
-//   2. the sign-mantissa bytes of the stream's first eight tiles are requested;
-//   3. the decode table goes to LDS (a3) as two byte tables (code length, symbol)
-//      at fixed LDS addresses, replicated to the full index width;
+//   2. the sign-mantissa bytes of the stream's tiles are requested: all eight of a group with non-temporal
+//      stores, the first four with ordinary stores (the others as tiles are finished);
+//   3. the decode table's first 256 entries go to LDS (a3) as 16-bit entries, code length in the low byte and
+//      symbol in the high byte, at a fixed LDS address, replicated to the full index width; longer codes
+//      are resolved from the tensor's full table in device memory;
 //   4. a wavefront prefix sum over the 64 lane-length bytes gives every lane the first and the last bit of
 //      its own bitstream (a6): what varies from lane to lane is where its input lies, its output positions
 //      are fixed;
