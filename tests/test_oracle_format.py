@@ -299,3 +299,34 @@ def test_damaged_objects_are_rejected():
         zo.encode(w, 4096, 1000, lengths)               # stream length must be a multiple of 512
     with pytest.raises(zo.OracleError):
         zo.encode(w, 4096 + 512, 1024, lengths)         # chunk length must be a multiple of the stream length
+
+
+def test_hand_worked_stream_bytes():
+    """the literal bytes of a stream derived by hand from the format's definition (tests/golden/worked_stream.txt):
+    bit order inside bytes, codes from both ends of a lane's bitstream, length bytes, sign-mantissa packing"""
+    spec = {}
+    for line in open(os.path.join(GOLDEN, "worked_stream.txt")):
+        if line.strip() and not line.startswith("#"):
+            key, rest = line.split(None, 1)
+            spec[key] = rest.strip()
+
+    def expand(text):
+        count, hexes = text.split("*")
+        return bytes.fromhex(hexes) * int(count)
+
+    i = np.arange(512)
+    exps = np.array([0x70, 0x75, 0x7A, 0x70, 0x70, 0x75, 0x70, 0x7A], np.uint16)[i % 8]
+    w = (((i % 2) << 15) | (exps << 7) | (i % 128)).astype(np.uint16)
+    lengths = zo.code_lengths(zo.histogram(zo.split(w)[0]), 8)
+    assert (lengths[0x70], lengths[0x75], lengths[0x7A]) == (1, 2, 2) and int((lengths > 0).sum()) == 3
+    blob = zo.encode(w, 512, 512, lengths)
+    h = zo.header(blob)
+    assert h["n_chunks"] == 1 and h["quantum"] == 1
+    entry = bytes(blob[h["table_offset"]: h["table_offset"] + h["table_stride"]])
+    chunk_at = int.from_bytes(entry[:8], "little")
+    assert chunk_at & 15 == 0                                   # coded
+    first, end = int.from_bytes(entry[8:12], "little"), int.from_bytes(entry[12:16], "little")
+    stream = bytes(blob[chunk_at + first: chunk_at + end])
+    assert stream == expand(spec["length_bytes"]) + expand(spec["payload"])
+    assert bytes(blob[h["sm_offset"]: h["sm_offset"] + 16]) == bytes.fromhex(spec["sm_head"].replace(" ", ""))
+    assert np.array_equal(zo.decode(blob), w)
