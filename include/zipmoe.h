@@ -223,6 +223,39 @@ int zm_decode_experts_stores(const void *const *blobs, const uint64_t *const *ch
                              void *const *out_bf16, int stores, void *stream);
 
 
+/* ---- A layer's resident experts as one handle (Sec. 3.1: the serialised objects made offline are what the
+ * run-time system keeps).  The handle holds what zm_decode_experts takes as arrays, so the hot call names
+ * expert ids and output buffers only.  It owns no device memory. ---- */
+typedef struct zm_layer zm_layer;
+
+/* Device bytes the blobs of a layer occupy: their sizes, each rounded up to 256.  blob_sizes: host array
+ * [n_tensors].  ZM_E_ARG on null pointers, n_tensors <= 0 or overflow. */
+int zm_layer_arena_bytes(const size_t *blob_sizes, int n_tensors, size_t *bytes);
+
+/* Registers a layer: checks every blob with zm_validate_blob, then copies them into `arena` (DEVICE memory of at
+ * least zm_layer_arena_bytes bytes, 256-byte aligned, owned by the caller and in use until zm_layer_destroy)
+ * with synchronous copies.  host_blobs, blob_sizes: host arrays [n_experts * tensors_per_expert], entry
+ * e*tensors_per_expert + m is tensor m of expert e; the host blobs are not needed after the call.
+ * ZM_E_ARG, ZM_E_SIZE (arena too small), ZM_E_FORMAT (a blob fails the check; nothing was uploaded),
+ * ZM_E_NOMEM, ZM_E_HIP. */
+int zm_layer_create(const void *const *host_blobs, const size_t *blob_sizes, int n_experts, int tensors_per_expert,
+                    void *arena, size_t arena_bytes, zm_layer **layer_out);
+
+/* Description of tensor `tensor` of expert `expert` and, if device_blob_out is not NULL, the device address
+ * of its blob.  ZM_E_ARG on bad indices. */
+int zm_layer_tensor_info(const zm_layer *layer, int expert, int tensor, zm_tensor_info *info_out,
+                         const void **device_blob_out);
+
+/* zm_decode_experts_stores on the layer's experts: expert_ids, n_selected, out_bf16, stores and stream as
+ * there, same limits and errors; asynchronous, allocates nothing. */
+int zm_layer_decode(const zm_layer *layer, const int32_t *expert_ids, int n_selected, void *const *out_bf16,
+                    int stores, void *stream);
+
+/* Frees the handle's host memory; the arena goes back to the caller (who waits for pending decodes before
+ * reusing it).  NULL is allowed. */
+void zm_layer_destroy(zm_layer *layer);
+
+
 /* What a decode call for the tensors infos[0..n_tensors) would launch, by the rule the decode calls use
  * themselves and without launching anything (for benchmarks and profiles that have to name the kernel):
  * one entry per kernel launch, in launch order.  Host only. */

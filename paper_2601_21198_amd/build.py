@@ -9,7 +9,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 # ZIPMOE_LIBRARY points the binding at another build of the same sources (same ABI)
 LIB_PATH = os.environ.get("ZIPMOE_LIBRARY", os.path.join(_HERE, "libzipmoe.so"))
-SOURCES = [os.path.join(CSRC, f) for f in ("zipmoe_host.cpp", "zipmoe_plan.cpp", "zipmoe_sched.cpp", "zipmoe_decode.hip", "zipmoe_cache.hip", "zipmoe_staged.hip", "zipmoe_probe.hip")]
+SOURCES = [os.path.join(CSRC, f) for f in ("zipmoe_host.cpp", "zipmoe_plan.cpp", "zipmoe_sched.cpp", "zipmoe_decode.hip", "zipmoe_cache.hip", "zipmoe_staged.hip", "zipmoe_probe.hip", "zipmoe_layer.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",

@@ -24,6 +24,7 @@ STORES_AUTO, STORES_CACHED, STORES_STREAMING = 0, 1, 2
 
 EXPORTS = ("zm_version", "zm_strerror", "zm_exponent_histogram", "zm_build_codebook", "zm_encode_bound",
            "zm_encode", "zm_blob_info", "zm_validate_blob", "zm_decode_experts", "zm_decode_experts_stores", "zm_decode_launch_shapes", "zm_decode_tensors", "zm_decode_host_tensors",
+           "zm_layer_arena_bytes", "zm_layer_create", "zm_layer_tensor_info", "zm_layer_decode", "zm_layer_destroy",
            "zm_decode_exponents_host", "zm_recover", "zm_mover_probe", "zm_cache_dispatch", "zm_cache_arena_bytes", "zm_cache_image_bytes",
            "zm_cache_pack_expert", "zm_cache_create",
            "zm_cache_fetch", "zm_cache_pool_of", "zm_cache_destroy", "zm_plan_selection_probabilities",
@@ -136,6 +137,13 @@ def lib() -> ctypes.CDLL:
         L.zm_decode_exponents_host.argtypes = [c.c_void_p, c.c_size_t, c.c_uint32, c.c_uint32, u8p, c.c_int]
         L.zm_mover_probe.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_size_t, c.c_int, c.c_int, c.c_void_p]
         L.zm_recover.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p, c.c_void_p]
+        L.zm_layer_arena_bytes.argtypes = [c.POINTER(c.c_size_t), c.c_int, c.POINTER(c.c_size_t)]
+        L.zm_layer_create.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_size_t), c.c_int, c.c_int, c.c_void_p, c.c_size_t,
+                                      c.POINTER(c.c_void_p)]
+        L.zm_layer_tensor_info.argtypes = [c.c_void_p, c.c_int, c.c_int, c.POINTER(TensorInfo), c.POINTER(c.c_void_p)]
+        L.zm_layer_decode.argtypes = [c.c_void_p, c.POINTER(c.c_int32), c.c_int, c.POINTER(c.c_void_p), c.c_int, c.c_void_p]
+        L.zm_layer_destroy.argtypes = [c.c_void_p]
+        L.zm_layer_destroy.restype = None
         L.zm_cache_dispatch.argtypes = [u64p, c.c_int, c.POINTER(c.c_int32), c.c_int, c.c_int]
         L.zm_cache_arena_bytes.argtypes = [c.POINTER(CacheConfig), c.POINTER(TensorInfo), c.POINTER(c.c_size_t)]
         L.zm_cache_image_bytes.argtypes = [c.POINTER(CacheConfig), c.POINTER(TensorInfo), c.POINTER(c.c_size_t)]
@@ -157,7 +165,7 @@ def lib() -> ctypes.CDLL:
         L.zm_plan_pools.argtypes = [dp, c.c_int, c.c_int, c.POINTER(PlanCosts), c.c_double, dp, c.c_int, c.c_int,
                                     dp, c.POINTER(c.c_int32), dp]
         for name in EXPORTS:
-            if name not in ("zm_strerror", "zm_encode_bound", "zm_cache_destroy"):
+            if name not in ("zm_strerror", "zm_encode_bound", "zm_cache_destroy", "zm_layer_destroy"):
                 getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -377,6 +385,49 @@ class ExpertLayer:
 
     def decode(self, expert_ids, out_buffers, starts, stream: int = 0, stores: int = STORES_AUTO) -> None:
         self.make_call(expert_ids, out_buffers, starts, stores)(stream)
+
+
+class Layer:
+    """zm_layer: the library's own handle for one layer's resident experts.  The arena is a torch tensor this
+    object keeps alive; everything else is argument marshalling."""
+
+    def __init__(self, expert_blobs: Sequence[Sequence[np.ndarray]], device: str = "cuda:0"):
+        import torch
+        self.n_experts = len(expert_blobs)
+        self.tensors_per_expert = len(expert_blobs[0])
+        flat = [np.ascontiguousarray(b, np.uint8) for tensors in expert_blobs for b in tensors]
+        n = len(flat)
+        sizes = (ctypes.c_size_t * n)(*[int(b.size) for b in flat])
+        need = ctypes.c_size_t(0)
+        _check(lib().zm_layer_arena_bytes(sizes, n, ctypes.byref(need)), "zm_layer_arena_bytes")
+        self.arena = torch.empty(need.value, dtype=torch.uint8, device=torch.device(device))
+        ptrs = (ctypes.c_void_p * n)(*[b.ctypes.data for b in flat])
+        handle = ctypes.c_void_p(None)
+        _check(lib().zm_layer_create(ptrs, sizes, self.n_experts, self.tensors_per_expert,
+                                     ctypes.c_void_p(self.arena.data_ptr()), need.value, ctypes.byref(handle)), "zm_layer_create")
+        self._handle = handle
+
+    def tensor_info(self, expert: int, tensor: int) -> TensorInfo:
+        info = TensorInfo()
+        _check(lib().zm_layer_tensor_info(self._handle, expert, tensor, ctypes.byref(info), None), "zm_layer_tensor_info")
+        return info
+
+    def decode(self, expert_ids, out_ptrs, stream: int = 0, stores: int = STORES_AUTO) -> None:
+        """out_ptrs: device addresses, one per selected expert and tensor (expert-major)."""
+        ids = (ctypes.c_int32 * len(expert_ids))(*[int(e) for e in expert_ids])
+        outs = (ctypes.c_void_p * len(out_ptrs))(*[int(p) for p in out_ptrs])
+        _check(lib().zm_layer_decode(self._handle, ids, len(expert_ids), outs, stores, ctypes.c_void_p(stream)), "zm_layer_decode")
+
+    def close(self) -> None:
+        if self._handle:
+            lib().zm_layer_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def cache_dispatch(counts, slots, tolerance: int, expert: int) -> int:

@@ -342,6 +342,39 @@ def test_limits_of_one_call():
     torch.cuda.synchronize()
 
 
+def test_layer_handle_decodes_like_the_array_call():
+    """zm_layer_create / zm_layer_decode: the library's own handle for a layer's resident experts"""
+    import torch
+    rng = np.random.default_rng(5)
+    n_experts, per = 5, 3
+    tensors = [[synth.special_tensor(KINDS[int(rng.integers(len(KINDS)))], int(rng.integers(1, 90000)), seed=50 + 3 * e + m)
+                for m in range(per)] for e in range(n_experts)]
+    blobs = [[(zm.compress(w, 16384, 4096, 8)[0] if (e + m) % 2 else zo.encode_tensor(w, 16384, 4096, 8)[0])
+              for m, w in enumerate(ts)] for e, ts in enumerate(tensors)]
+    layer = zm.Layer(blobs)
+    for e in range(n_experts):
+        for m in range(per):
+            a, b = layer.tensor_info(e, m), zm.blob_info(blobs[e][m][:384])
+            assert bytes(a) == bytes(b)
+    ids = [3, 0, 3, 4]                                           # a duplicate is decoded twice
+    outs = [[torch.full((tensors[e][m].size + 2 * GUARD,), GUARD_WORD, dtype=torch.int16, device="cuda") for m in range(per)]
+            for e in ids]
+    ptrs = [o.data_ptr() + 2 * GUARD for row in outs for o in row]
+    for stores in (zm.STORES_AUTO, zm.STORES_STREAMING):
+        layer.decode(ids, ptrs, torch.cuda.current_stream().cuda_stream, stores)
+        torch.cuda.synchronize()
+        for j, e in enumerate(ids):
+            for m in range(per):
+                a = outs[j][m].cpu().numpy().view(np.uint16)
+                assert np.all(a[:GUARD] == GUARD_WORD) and np.all(a[-GUARD:] == GUARD_WORD)
+                assert np.array_equal(a[GUARD:-GUARD], tensors[e][m])
+                assert np.array_equal(a[GUARD:-GUARD], zo.decode(blobs[e][m]))
+                outs[j][m][GUARD:-GUARD].zero_()
+    with pytest.raises(zm.ZipMoEError):
+        layer.decode([n_experts], ptrs[:per])                    # id out of range
+    layer.close()
+
+
 def test_decode_call_can_be_captured_in_a_hip_graph():
     """the hot call allocates nothing and copies nothing, so it can be recorded into a graph; every replay,
     with eager work and synchronisations in between, must give the eager result"""

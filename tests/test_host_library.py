@@ -218,6 +218,41 @@ def test_decode_entry_points_refuse_bad_arguments_before_any_launch():
     assert L.zm_mover_probe(ctypes.c_void_p(good), ctypes.c_void_p(good), 16, 16, 3, 0, None) == zm.E_ARG
 
 
+def test_layer_handle_checks_everything_before_it_touches_the_device():
+    """zm_layer_create validates sizes, alignment and every blob on the host first: all of these fail (or succeed
+    trivially) without a device"""
+    L = zm.lib()
+    w = synth.special_tensor("gauss", 20000, 1)
+    blob, _ = zm.compress(w, 4096, 4096, 8)
+    sizes = (ctypes.c_size_t * 2)(int(blob.size), int(blob.size))
+    need = ctypes.c_size_t(0)
+    assert L.zm_layer_arena_bytes(sizes, 2, ctypes.byref(need)) == zm.OK and need.value == 2 * int(blob.size)
+    odd = (ctypes.c_size_t * 2)(1000, 257)
+    assert L.zm_layer_arena_bytes(odd, 2, ctypes.byref(need)) == zm.OK and need.value == 1024 + 512
+    assert L.zm_layer_arena_bytes(None, 2, ctypes.byref(need)) == zm.E_ARG
+    assert L.zm_layer_arena_bytes(sizes, 0, ctypes.byref(need)) == zm.E_ARG
+    ptrs = (ctypes.c_void_p * 2)(blob.ctypes.data, blob.ctypes.data)
+    handle = ctypes.c_void_p(None)
+    arena = ctypes.c_void_p(1 << 20)                 # an aligned address that is never dereferenced by these calls
+    big = 1 << 30
+    assert L.zm_layer_create(None, sizes, 2, 1, arena, big, ctypes.byref(handle)) == zm.E_ARG
+    assert L.zm_layer_create(ptrs, sizes, 0, 1, arena, big, ctypes.byref(handle)) == zm.E_ARG
+    assert L.zm_layer_create(ptrs, sizes, 2, 1, None, big, ctypes.byref(handle)) == zm.E_ARG
+    assert L.zm_layer_create(ptrs, sizes, 2, 1, ctypes.c_void_p((1 << 20) + 16), big, ctypes.byref(handle)) == zm.E_ARG
+    assert L.zm_layer_create(ptrs, sizes, 2, 1, arena, 2 * int(blob.size) - 1, ctypes.byref(handle)) == zm.E_SIZE
+    damaged = blob.copy()
+    damaged[130] ^= 0x3F                             # a code length: the codebook no longer matches the table
+    bad = (ctypes.c_void_p * 2)(blob.ctypes.data, damaged.ctypes.data)
+    assert L.zm_layer_create(bad, sizes, 2, 1, arena, big, ctypes.byref(handle)) == zm.E_FORMAT
+    short = (ctypes.c_size_t * 2)(int(blob.size), int(blob.size) - 256)
+    assert L.zm_layer_create(ptrs, short, 2, 1, arena, big, ctypes.byref(handle)) == zm.E_FORMAT
+    assert handle.value is None
+    info = zm.TensorInfo()
+    assert L.zm_layer_tensor_info(None, 0, 0, ctypes.byref(info), None) == zm.E_ARG
+    assert L.zm_layer_decode(None, None, 0, None, 0, None) == zm.E_ARG
+    L.zm_layer_destroy(None)
+
+
 def test_launch_shapes_follow_code_length_stream_length_and_output_size():
     """zm_decode_launch_shapes is host logic: the same rule the decode calls launch by"""
     def info_of(kind, n, C, W, max_len):
