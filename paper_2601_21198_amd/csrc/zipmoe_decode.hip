@@ -130,6 +130,7 @@ __device__ __forceinline__ void recover_and_store_partial(uint16_t *dst, uint2 e
 }
 
 constexpr uint32_t kTableEntries = 256;   // the LDS table resolves the first eight bits of a code
+constexpr uint32_t kLongSlots = 16;       // eight-bit beginnings of longer codes that get a block of the second LDS table
 
 // Lock-step decoder state of one lane (a5): two chains, one reading the lane's bitstream upwards from its
 // first bit (the first half of the lane's symbols, in order), one reading it downwards from its last bit (the
@@ -137,7 +138,9 @@ constexpr uint32_t kTableEntries = 256;   // the LDS table resolves the first ei
 // R = 4: every code has at most 8 bits, four symbols per 32-bit window.  R = 2: codes of up to ZM_MAX_CODE_LEN
 // bits, two symbols per window; the LDS table still resolves eight bits, and a lane that meets a longer code
 // (its table entry carries a length above 8: no code of at most 8 bits begins with these bits) takes its entry
-// from the tensor's full decode table in device memory instead.  Long codes are the rare ones by construction.
+// from a second LDS table that holds, for each eight-bit beginning of longer codes, the 16 entries its further
+// bits select -- or, when a tensor has more than kLongSlots such beginnings, from the tensor's full decode table in
+// device memory.  Long codes are the rare ones by construction and sit together at the end of the code space.
 template <int R>
 struct Decoder {
     const uint32_t *words;        // the stream as staged in LDS (length bytes included)
@@ -147,6 +150,11 @@ struct Decoder {
     // downward chain: dhi is the word that holds the bits just below the read position, of which its low dpos
     // bits (0..31) are still unread, dlo the word below it, dnext the index of the word below that
     uint32_t dlo = 0, dhi = 0, dpos = 0, dnext = 0;
+    // R = 2 only: the LDS table of the codes longer than eight bits (kLongSlots blocks of 16 entries, one block per
+    // eight-bit beginning that such codes share) and the bits it resolves beyond the first eight; 0 = the tensor has
+    // more such beginnings than blocks, and long codes are looked up in device memory
+    const uint16_t *sub = nullptr;
+    uint32_t sub_bits = 0;
 
     // first_bit, end_bit: where this lane's bitstream starts and ends, counted from the first payload bit
     __device__ __forceinline__ void start(uint32_t first_bit, uint32_t end_bit)
@@ -171,8 +179,14 @@ struct Decoder {
         if constexpr (R == 2) {
             if (__builtin_amdgcn_ballot_w64((v & 0xffu) > 8u)) {          // some lane of the wave has a long code
                 if ((v & 0xffu) > 8u) {
-                    const uint32_t full = full_table[(win >> (acc & 31u)) & ((1u << max_len) - 1u)];
-                    v = __builtin_amdgcn_perm(0u, full, 0x0c0c0001u);      // symbol | length << 8  ->  length | symbol << 8
+                    if (sub_bits) {
+                        // the entry's high byte names the block of this beginning; the code's further bits index it
+                        const uint32_t more = __builtin_amdgcn_ubfe(win, acc + 8u, 4) & ((1u << sub_bits) - 1u);
+                        v = sub[((v >> 8) & (kLongSlots - 1u)) * 16u + more];
+                    } else {
+                        const uint32_t full = full_table[(win >> (acc & 31u)) & ((1u << max_len) - 1u)];
+                        v = __builtin_amdgcn_perm(0u, full, 0x0c0c0001u);      // symbol | length << 8  ->  length | symbol << 8
+                    }
                 }
             }
         }
@@ -245,6 +259,10 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     // one 16-bit read gives a code's length and its symbol.  (Two byte tables, one read each, were 2-4 % slower:
     // twice the LDS instructions, whose random accesses collide on banks.)
     __shared__ __align__(16) uint16_t tab[kTableEntries];
+    // second table for codes longer than eight bits (R = 2): kLongSlots blocks of 16 entries, and the eight-bit
+    // beginning each block belongs to
+    __shared__ __align__(16) uint16_t sub[R == 2 ? kLongSlots * 16 : 4];
+    __shared__ uint16_t long_prefix[R == 2 ? kLongSlots : 2];
     extern __shared__ __align__(16) uint32_t stream_lds[];
 
     const uint32_t lane = threadIdx.x & 63u;
@@ -329,11 +347,48 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     // replicated over the index bits above the longest code.  Four entries per lane, all loads issued before the
     // first is used.  Every wave of the workgroup writes the same bytes (LDS word writes are atomic), so a wave may
     // read as soon as its own writes are done: no workgroup barrier.
+    uint32_t sub_bits = 0;
     {
         const uint16_t *src = reinterpret_cast<const uint16_t *>(t.lut);
         const uint32_t mask = (1u << max_len) - 1u;
         const uint32_t i = 4u * lane;
-        const uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
+        uint32_t a = src[i & mask], b = src[(i + 1) & mask], c = src[(i + 2) & mask], d = src[(i + 3) & mask];
+        if constexpr (R == 2) {
+            // Entries with a length above eight mark the eight-bit beginnings of longer codes.  They are numbered in
+            // index order; if there are at most kLongSlots of them, entry number s gets block s of the second table
+            // (its symbol byte is replaced by s) and the block is filled with the 2^(max_len - 8) entries of the
+            // full table that share these eight bits.
+            const uint32_t la = (a >> 8) > 8u, lb = (b >> 8) > 8u, lc = (c >> 8) > 8u, ld = (d >> 8) > 8u;
+            const uint64_t ma = __builtin_amdgcn_ballot_w64(la), mb = __builtin_amdgcn_ballot_w64(lb),
+                           mc = __builtin_amdgcn_ballot_w64(lc), md = __builtin_amdgcn_ballot_w64(ld);
+            const uint32_t n_long = __builtin_popcountll(ma) + __builtin_popcountll(mb) + __builtin_popcountll(mc) + __builtin_popcountll(md);
+            if (n_long != 0 && n_long <= kLongSlots && max_len > 8u) {
+                const uint64_t below = (1ull << lane) - 1ull;
+                const uint32_t sa = __builtin_popcountll(ma & below) + __builtin_popcountll(mb & below) +
+                                    __builtin_popcountll(mc & below) + __builtin_popcountll(md & below);
+                const uint32_t sb = sa + la, sc = sb + lb, sd = sc + lc;
+                if (la) { long_prefix[sa] = static_cast<uint16_t>(i); a = (a & 0xff00u) | sa; }
+                if (lb) { long_prefix[sb] = static_cast<uint16_t>(i + 1u); b = (b & 0xff00u) | sb; }
+                if (lc) { long_prefix[sc] = static_cast<uint16_t>(i + 2u); c = (c & 0xff00u) | sc; }
+                if (ld) { long_prefix[sd] = static_cast<uint16_t>(i + 3u); d = (d & 0xff00u) | sd; }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+                sub_bits = max_len - 8u;
+                // lane l fills entries 4l..4l+3 of the second table: block (4l)/16, further bits (4l)%16 + 0..3
+                const uint32_t block = lane >> 2, first = (lane & 3u) * 4u;
+                uint32_t e[4];
+#pragma unroll
+                for (uint32_t j = 0; j < 4; ++j) {
+                    const uint32_t more = first + j;
+                    e[j] = 0u;
+                    if (block < n_long && more < (1u << sub_bits))
+                        e[j] = src[(static_cast<uint32_t>(long_prefix[block]) + (more << 8)) & mask];
+                }
+                const uint32_t e01 = e[0] | (e[1] << 16), e23 = e[2] | (e[3] << 16);
+                reinterpret_cast<uint2 *>(sub)[lane] = make_uint2(__builtin_amdgcn_perm(e01, e01, 0x02030001u), __builtin_amdgcn_perm(e23, e23, 0x02030001u));
+            }
+        }
         const uint32_t ab = a | (b << 16), cd = c | (d << 16);
         reinterpret_cast<uint2 *>(tab)[lane] = make_uint2(__builtin_amdgcn_perm(ab, ab, 0x02030001u), __builtin_amdgcn_perm(cd, cd, 0x02030001u));
     }
@@ -354,6 +409,7 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
     const uint16_t *full_table = reinterpret_cast<const uint16_t *>(t.lut);
     Decoder<R> dec;
     dec.words = words; dec.last_word = P.stream_cap_words - 1u;
+    dec.sub = sub; dec.sub_bits = sub_bits;
     if (mode == ZM_MODE_CODED) {
         // a6: this lane's bitstream has 8 * tiles + quantum * (its length byte) bits and starts where
         // the bitstreams of the lanes below it end
@@ -471,6 +527,9 @@ inline size_t stream_cap_words(uint32_t stream_values, uint32_t max_len_bound, u
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;
+// LDS a workgroup holds beside its streams: the first table, and with long codes the second one and its index
+template <int R>
+constexpr size_t kStaticLds = 2 * kTableEntries + (R == 2 ? 2 * kLongSlots * 16 + 2 * kLongSlots : 0);
 constexpr uint64_t kLastLevelCacheBytes = 256ull << 20;   // MI355X Infinity Cache
 
 template <int R, int kWaves, bool kStreaming>
@@ -493,7 +552,7 @@ template <int R, int kWaves>
 int launch_tasks(Launch &L, size_t cap, int stores, hipStream_t stream, Recorder *rec)
 {
     const size_t lds = 4 * kWaves * cap;                       // dynamic part: the streams
-    if (lds + 2 * kTableEntries > kLdsLimit) {
+    if (lds + kStaticLds<R> > kLdsLimit) {
         if constexpr (kWaves > 1) return launch_tasks<R, kWaves / 2>(L, cap, stores, stream, rec);
         else return ZM_E_ARG;                   // stream too long to stage in LDS
     }
@@ -509,7 +568,7 @@ int launch_tasks(Launch &L, size_t cap, int stores, hipStream_t stream, Recorder
     if (rec) {
         if (rec->n < rec->cap)
             rec->out[rec->n] = zm_launch_shape{static_cast<uint32_t>(R), static_cast<uint32_t>(kWaves), streaming ? 1u : 0u, blocks,
-                                               L.n_tasks, static_cast<uint32_t>(lds + 2 * kTableEntries)};
+                                               L.n_tasks, static_cast<uint32_t>(lds + kStaticLds<R>)};
         ++rec->n;
         return ZM_OK;
     }

@@ -146,4 +146,7 @@ def special_tensor(kind: str, n: int, seed: int = 0) -> np.ndarray:
     if kind == "wide":          # some forty distinct exponents with long tails: log-normal magnitudes
         mag = np.exp(rng.normal(0.0, 3.0, n)).astype(np.float32)
         return bf16_round(mag * rng.choice(np.array([-1.0, 1.0], np.float32), n))
+    if kind == "many_long":     # one exponent half of the time, the other 255 equally rare: with a limit above 8 bits
+        e = np.where(rng.random(n) < 0.5, 0x70, rng.integers(0, 256, n)).astype(np.uint16)   # there are many codes of 9 bits
+        return (e << 7) | rng.integers(0, 128, n, dtype=np.uint16) | (rng.integers(0, 2, n, dtype=np.uint16) << 15)
     raise ValueError(kind)

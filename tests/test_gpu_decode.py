@@ -52,7 +52,7 @@ def gpu_decode_tensors(blobs, repeat_ids=None, stores=None):
     return res
 
 
-KINDS = ["all_equal", "two_exponents", "uniform_u16", "rare_last", "gauss", "wide"]
+KINDS = ["all_equal", "two_exponents", "uniform_u16", "rare_last", "gauss", "wide", "many_long"]
 SIZES = [0, 1, 7, 8, 9, 511, 512, 513, 4095, 4096, 4097, 9000, 3 * 16384 + 1234]
 
 
