@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0        # MI355X published peak HBM3E bandwidth
 # copy of known size; the summaries are under profiles/).  Valid only for the kernel source they were taken
 # with: the entry is reported only while the source's hash still matches, else "traffic" is null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256_16": "588350b1882af9cd",
-    "bytes_per_launch": {"cfg5": 117.14e6, "cfg3": 170.39e6, "cfg4": 1195.79e6, "split-cfg4": 234.96e6},
+    "kernel_sha256_16": "333d1b74932d3db6",
+    "bytes_per_launch": {"cfg5": 117.14e6, "cfg3": 170.39e6, "cfg4": 1195.78e6, "split-cfg4": 234.96e6},
 }
 
 

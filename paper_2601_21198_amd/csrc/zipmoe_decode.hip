@@ -131,6 +131,7 @@ __device__ __forceinline__ void recover_and_store_partial(uint16_t *dst, uint2 e
 
 constexpr uint32_t kTableEntries = 256;   // the LDS table resolves the first eight bits of a code
 constexpr uint32_t kLongSlots = 16;       // eight-bit beginnings of longer codes that get a block of the second LDS table
+constexpr uint32_t kLongFlag = 0x80u;     // set in the length byte of a first-table entry whose code has more than eight bits
 
 // Lock-step decoder state of one lane (a5): two chains, one reading the lane's bitstream upwards from its
 // first bit (the first half of the lane's symbols, in order), one reading it downwards from its last bit (the
@@ -171,26 +172,17 @@ struct Decoder {
         dnext = w - 2u;
     }
 
-    // One lookup: the entry (length | symbol << 8) of the code that starts at bit (acc & 31) of win.
-    __device__ __forceinline__ uint32_t lookup(const uint16_t *tab, const uint16_t *full_table, uint32_t max_len,
-                                               uint32_t win, uint32_t acc)
+    // R = 2: the entry of a code longer than eight bits, whose first-table entry v carries kLongFlag.
+    __device__ __forceinline__ uint32_t long_code(const uint16_t *full_table, uint32_t max_len, uint32_t win, uint32_t acc,
+                                                  uint32_t v) const
     {
-        uint32_t v = tab[__builtin_amdgcn_ubfe(win, acc, 8)];
-        if constexpr (R == 2) {
-            if (__builtin_amdgcn_ballot_w64((v & 0xffu) > 8u)) {          // some lane of the wave has a long code
-                if ((v & 0xffu) > 8u) {
-                    if (sub_bits) {
-                        // the entry's high byte names the block of this beginning; the code's further bits index it
-                        const uint32_t more = __builtin_amdgcn_ubfe(win, acc + 8u, 4) & ((1u << sub_bits) - 1u);
-                        v = sub[((v >> 8) & (kLongSlots - 1u)) * 16u + more];
-                    } else {
-                        const uint32_t full = full_table[(win >> (acc & 31u)) & ((1u << max_len) - 1u)];
-                        v = __builtin_amdgcn_perm(0u, full, 0x0c0c0001u);      // symbol | length << 8  ->  length | symbol << 8
-                    }
-                }
-            }
+        if (sub_bits) {
+            // the entry's high byte names the block of this beginning; the code's further bits index it
+            const uint32_t more = __builtin_amdgcn_ubfe(win, acc + 8u, 4) & ((1u << sub_bits) - 1u);
+            return sub[((v >> 8) & (kLongSlots - 1u)) * 16u + more];
         }
-        return v;
+        const uint32_t full = full_table[(win >> (acc & 31u)) & ((1u << max_len) - 1u)];
+        return __builtin_amdgcn_perm(0u, full, 0x0c0c0001u);      // symbol | length << 8  ->  length | symbol << 8
     }
 
     // One round: R symbols of each chain.  up / down receive the R entries in the order read.
@@ -209,10 +201,20 @@ struct Decoder {
         uint32_t acc = 0, dacc = 0;
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-            up[k] = lookup(tab, full_table, max_len, win, acc);
-            down[k] = lookup(tab, full_table, max_len, dwin, dacc);
-            acc += up[k];
-            dacc += down[k];
+            // the entries (length | symbol << 8) of the codes that start at bit (acc & 31) of the two windows
+            uint32_t v = tab[__builtin_amdgcn_ubfe(win, acc, 8)];
+            uint32_t dv = tab[__builtin_amdgcn_ubfe(dwin, dacc, 8)];
+            if constexpr (R == 2) {
+                // both look-ups are out before either is tested: one branch per step, rarely taken
+                if ((v | dv) & kLongFlag) {
+                    if (v & kLongFlag) v = long_code(full_table, max_len, win, acc, v);
+                    if (dv & kLongFlag) dv = long_code(full_table, max_len, dwin, dacc, dv);
+                }
+            }
+            up[k] = v;
+            down[k] = dv;
+            acc += v;
+            dacc += dv;
         }
         // written without branches so that (with short codes) a whole tile pair is one basic block
         pos += acc & 0xffu;
@@ -362,6 +364,8 @@ __global__ void __launch_bounds__(64 * kWaves) zm_decode_kernel(const Launch P)
             const uint64_t ma = __builtin_amdgcn_ballot_w64(la), mb = __builtin_amdgcn_ballot_w64(lb),
                            mc = __builtin_amdgcn_ballot_w64(lc), md = __builtin_amdgcn_ballot_w64(ld);
             const uint32_t n_long = __builtin_popcountll(ma) + __builtin_popcountll(mb) + __builtin_popcountll(mc) + __builtin_popcountll(md);
+            // every such entry is flagged in its length byte (lengths stay below 16)
+            a |= la ? kLongFlag << 8 : 0u; b |= lb ? kLongFlag << 8 : 0u; c |= lc ? kLongFlag << 8 : 0u; d |= ld ? kLongFlag << 8 : 0u;
             if (n_long != 0 && n_long <= kLongSlots && max_len > 8u) {
                 const uint64_t below = (1ull << lane) - 1ull;
                 const uint32_t sa = __builtin_popcountll(ma & below) + __builtin_popcountll(mb & below) +
